@@ -1,0 +1,169 @@
+"""Pins for the oracle's Lloyd iteration and sweep (the k-means call of Algorithm 1, Sec. 4.2)."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_1905_12799_amd import synth
+
+
+def inertia_of(X, C, labels):
+    Xd, Cd = X.astype(np.float64), C.astype(np.float64)
+    return float(((Xd - Cd[labels]) ** 2).sum())
+
+
+def best_partition_inertia(X, k):
+    """Global optimum over all k^N labelings with the exact mean as centre (tiny N only)."""
+    N = X.shape[0]
+    Xd = X.astype(np.float64)
+    best = np.inf
+    for lab in itertools.product(range(k), repeat=N):
+        lab = np.array(lab)
+        J = 0.0
+        for j in range(k):
+            m = Xd[lab == j]
+            if len(m):
+                J += ((m - m.mean(axis=0)) ** 2).sum()
+        best = min(best, J)
+    return best
+
+
+def exact_mean_f32(rows):
+    """fp32( fp64(exact sum) / n ) with rationals: the centroid definition."""
+    out = []
+    for l in range(rows.shape[1]):
+        s = sum(Fraction(float(v)) for v in rows[:, l])
+        out.append(np.float32(float(s) / float(len(rows))))
+    return np.array(out, dtype=np.float32)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_brute_force_tiny(orc, seed):
+    rng = np.random.default_rng(seed)
+    X = rng.integers(0, 12, size=(9, 2)).astype(np.float32)
+    for k in (2, 3):
+        init = orc.kmeanspp_chain(X, k, seed)
+        labels, C, J, _ = orc.lloyd(X, k, 25, init)
+        assert J >= best_partition_inertia(X, k) - 1e-9
+        # fixed point: one more assignment and update changes nothing
+        Xd = X.astype(np.float64)
+        dist = ((Xd[:, None, :] - C.astype(np.float64)[None]) ** 2).sum(axis=2)
+        np.testing.assert_array_equal(labels, dist.argmin(axis=1))
+        for j in range(k):
+            if np.any(labels == j):
+                np.testing.assert_array_equal(C[j], exact_mean_f32(X[labels == j]))
+        assert abs(J - inertia_of(X, C, labels)) <= 1e-12 * max(J, 1.0)
+
+
+def test_half_step_trace_never_increases(orc):
+    p = synth.make_problem(synth.WORKLOADS["tiny"])
+    init = orc.kmeanspp_chain(p.X, 16, 11)
+    for k in (2, 7, 16):
+        _, _, J, trace = orc.lloyd(p.X, k, 20, init, want_trace=True)
+        assert trace.shape == (41,)
+        # tolerance: centroids are rounded to fp32, so a mean step may lose a relative 1e-7 of the loss
+        assert np.all(trace[1:] <= trace[:-1] * (1 + 1e-6))
+        assert trace[-1] == J
+        assert trace[-1] < trace[0]
+
+
+def test_planted_clusters_recovered(orc):
+    k, n_per, d, sigma = 6, 200, 4, 0.5
+    X, truth = synth.planted_clusters(n_per, k, d, sep=20 * sigma * 4, sigma=sigma, seed=9)
+    init = orc.kmeanspp_chain(X, k, 5)
+    labels, C, J, _ = orc.lloyd(X, k, 15, init)
+    # same partition up to relabelling
+    mapping = {}
+    for a, b in zip(labels.tolist(), truth.tolist()):
+        assert mapping.setdefault(a, b) == b
+    assert len(set(mapping.values())) == k
+    for j in range(k):
+        members = X[truth == mapping[j]].astype(np.float64)
+        assert np.all(np.abs(C[j] - members.mean(axis=0)) < 1e-5)
+    assert J == pytest.approx(((X.astype(np.float64) - C.astype(np.float64)[labels]) ** 2).sum(), rel=1e-12)
+    assert J / (k * n_per * d) == pytest.approx(sigma ** 2, rel=0.15)
+
+
+def test_k1_is_column_mean_and_kN_is_zero(orc):
+    rng = np.random.default_rng(1)
+    X = (rng.standard_normal((257, 5)) * 3 + 1).astype(np.float32)
+    labels, C, J, _ = orc.lloyd(X, 1, 3, np.array([17]))
+    np.testing.assert_array_equal(labels, 0)
+    np.testing.assert_array_equal(C[0], exact_mean_f32(X))
+    Xd = X.astype(np.float64)
+    assert J == pytest.approx(((Xd - C.astype(np.float64)) ** 2).sum(), rel=1e-13)
+    assert J == pytest.approx(257 * Xd.var(axis=0).sum(), rel=1e-6)
+    Xs = np.unique(rng.integers(0, 50, size=(40, 2)), axis=0).astype(np.float32)
+    n = Xs.shape[0]
+    labels, C, J, _ = orc.lloyd(Xs, n, 4, np.arange(n))
+    assert J == 0.0
+    np.testing.assert_array_equal(labels, np.arange(n))
+    np.testing.assert_array_equal(C, Xs)
+
+
+def test_exact_mean_is_order_independent_and_correctly_rounded(orc):
+    # values whose fp64 running sum depends on order: the fixed-point sum must not
+    rng = np.random.default_rng(8)
+    X = (rng.standard_normal((3000, 2)) * np.array([1e3, 1e-3])).astype(np.float32)
+    perm = rng.permutation(3000)
+    _, C1, _, _ = orc.lloyd(X, 1, 1, np.array([0]))
+    _, C2, _, _ = orc.lloyd(X[perm], 1, 1, np.array([0]))
+    np.testing.assert_array_equal(C1, C2)
+    np.testing.assert_array_equal(C1[0], exact_mean_f32(X))
+
+
+def test_integer_translation_invariance(orc):
+    p = synth.make_problem(synth.WORKLOADS["tiny"], N=600)
+    shift = np.array([3, -7, 11, 0, 2, -1, 5, 4], dtype=np.float32)
+    init = orc.kmeanspp_chain(p.X, 5, 2)
+    la, Ca, Ja, _ = orc.lloyd(p.X, 5, 10, init)
+    lb, Cb, Jb, _ = orc.lloyd(p.X + shift, 5, 10, init)
+    np.testing.assert_array_equal(la, lb)
+    np.testing.assert_allclose(Cb - shift, Ca, rtol=0, atol=2e-5)
+    assert Ja == pytest.approx(Jb, rel=1e-6)
+
+
+def test_one_dimensional_clusters_are_intervals(orc):
+    rng = np.random.default_rng(4)
+    X = np.sort(rng.uniform(0, 100, size=500)).astype(np.float32).reshape(-1, 1)
+    init = orc.kmeanspp_chain(X, 6, 1)
+    labels, _, _, _ = orc.lloyd(X, 6, 12, init)
+    changes = int((labels[1:] != labels[:-1]).sum())
+    assert changes == len(set(labels.tolist())) - 1
+
+
+def test_ties_go_to_lowest_index_and_empty_cluster_keeps_centroid(orc):
+    # points 0 and 4 are the first two centres; point 2 is equidistant -> label 0
+    X = np.array([[0.0], [1.0], [2.0], [3.0], [4.0]], dtype=np.float32)
+    labels, C, _, _ = orc.lloyd(X, 2, 0, np.array([0, 4]))
+    np.testing.assert_array_equal(labels, [0, 0, 0, 1, 1])
+    # duplicate initial centres: the second never wins a point and must keep its value
+    X2 = np.array([[1.0], [1.0], [5.0]], dtype=np.float32)
+    # (first Lloyd step: all three points tie and go to centre 0, centre 1 is empty)
+    labels, C, J, _ = orc.lloyd(X2, 2, 1, np.array([0, 1]))
+    assert C[1, 0] == 1.0
+    assert C[0, 0] == np.float32(7.0 / 3.0)
+    np.testing.assert_array_equal(labels, [1, 1, 0])       # final assignment against (7/3, 1)
+
+
+def test_value_outside_fixed_point_range_is_an_error(orc):
+    X = np.array([[1e-30], [1.0]], dtype=np.float32)
+    with pytest.raises(RuntimeError):
+        orc.lloyd(X, 1, 1, np.array([0]))
+
+
+def test_sweep_matches_single_runs_and_packing(orc):
+    p = synth.make_problem(synth.WORKLOADS["tiny"], N=500)
+    seed = 21
+    sw = orc.kmeans_sweep(p.X, 3, 7, 6, seed=seed, want_trace=True)
+    chain = orc.kmeanspp_chain(p.X, 7, seed)
+    for k in range(3, 8):
+        labels, C, J, half = orc.lloyd(p.X, k, 6, chain, want_trace=True)
+        np.testing.assert_array_equal(sw["labels"][k - 3], labels)
+        np.testing.assert_array_equal(orc.unpack_centroids(sw["centroids"], 3, k, 8), C)
+        assert sw["inertia"][k - 3] == J
+        np.testing.assert_array_equal(sw["trace"][k - 3], half[0::2])
+    # explicit initial indices reproduce the seeded sweep
+    sw2 = orc.kmeans_sweep(p.X, 3, 7, 6, init_idx=chain)
+    np.testing.assert_array_equal(sw2["centroids"], sw["centroids"])
