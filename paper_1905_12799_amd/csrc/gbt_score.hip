@@ -1,0 +1,100 @@
+// Tree-ensemble scoring of a trajectory of configurations (cost-model query, Sec. 4.1 of the paper).
+//
+// One configuration per lane.  A workgroup keeps a tile of P configurations in LDS, feature-major
+// (xs[f][p]): the walk reads xs[feat][lane], whose bank is lane % 32 whatever `feat` is, so these
+// gathers never conflict.  The forest is streamed through LDS in chunks of whole trees with each
+// internal node packed as (feature, threshold bits); every lane adds the leaf values to its own fp32
+// running sum in tree order, which makes the result independent of the launch shape.
+#include "rls_internal.h"
+
+namespace rls {
+
+namespace {
+
+constexpr int kForestChunkBytes = 64 * 1024;
+
+__global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int64_t N, int d, int64_t ldx,
+                                 float *__restrict__ score, int trees_per_chunk)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int P = blockDim.x;
+    const int n_int = (1 << f.depth) - 1;
+    const int n_leaf = 1 << f.depth;
+    float *xs = reinterpret_cast<float *>(smem);                                // [d][P]
+    uint2 *nodes = reinterpret_cast<uint2 *>(xs + (size_t)d * P);               // [trees_per_chunk][n_int]
+    float *leaves = reinterpret_cast<float *>(nodes + (size_t)trees_per_chunk * n_int);   // [trees_per_chunk][n_leaf]
+
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * P + tid;
+    const bool valid = row < N;
+    {
+        const float *x = X + (valid ? row : 0) * ldx;
+        if (valid && (d % 4 == 0) && (ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0)) {
+            const float4 *x4 = reinterpret_cast<const float4 *>(x);
+            for (int c = 0; c < d / 4; ++c) {
+                const float4 v = x4[c];
+                xs[(4 * c + 0) * P + tid] = v.x;
+                xs[(4 * c + 1) * P + tid] = v.y;
+                xs[(4 * c + 2) * P + tid] = v.z;
+                xs[(4 * c + 3) * P + tid] = v.w;
+            }
+        } else {
+            for (int c = 0; c < d; ++c) xs[c * P + tid] = valid ? x[c] : 0.0f;
+        }
+    }
+
+    float sum = f.base;
+    for (int t0 = 0; t0 < f.n_trees; t0 += trees_per_chunk) {
+        const int tc = min(trees_per_chunk, f.n_trees - t0);
+        __syncthreads();   // previous chunk fully consumed (and, first time, xs written)
+        for (int e = tid; e < tc * n_int; e += P) {
+            int ft = f.feat[(size_t)t0 * n_int + e];
+            ft = min(max(ft, 0), d - 1);
+            nodes[e] = make_uint2((unsigned)ft, __float_as_uint(f.thr[(size_t)t0 * n_int + e]));
+        }
+        for (int e = tid; e < tc * n_leaf; e += P) leaves[e] = f.leaf[(size_t)t0 * n_leaf + e];
+        __syncthreads();
+        for (int t = 0; t < tc; ++t) {
+            const uint2 *tn = nodes + (size_t)t * n_int;
+            int n = 0;
+            for (int lev = 0; lev < f.depth; ++lev) {
+                const uint2 nd = tn[n];
+                const float xv = xs[nd.x * P + tid];
+                n = 2 * n + 1 + ((xv < __uint_as_float(nd.y)) ? 0 : 1);
+            }
+            sum = sum + leaves[t * n_leaf + (n - n_int)];
+        }
+    }
+    if (valid) score[row] = sum;
+}
+
+}  // namespace
+
+hipError_t launch_gbt_score(const ForestArgs *forests_host, int32_t batch, const float *X, int64_t N, int32_t d,
+                            int64_t ldx, int64_t x_batch_stride, float *score, hipStream_t s)
+{
+    const int P = d <= 16 ? 1024 : 512;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gbt_score_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    for (int32_t b = 0; b < batch; ++b) {
+        const ForestArgs &f = forests_host[b];
+        const int64_t tree_bytes = (((int64_t)1 << f.depth) - 1) * 8 + ((int64_t)1 << f.depth) * 4;
+        int tpc = (int)(kForestChunkBytes / tree_bytes);
+        if (tpc < 1) tpc = 1;
+        if (tpc > f.n_trees) tpc = f.n_trees;
+        const size_t lds = (size_t)d * P * 4 + (size_t)tpc * tree_bytes;
+        const unsigned grid = (unsigned)((N + P - 1) / P);
+        hipLaunchKernelGGL(gbt_score_kernel, dim3(grid), dim3(P), lds, s, f, X + (int64_t)b * x_batch_stride, N, (int)d,
+                           ldx, score + (int64_t)b * N, tpc);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace rls

@@ -1,0 +1,224 @@
+// k-means++ seeding chain (D^2 sampling) for the k-means runs of Algorithm 1 (Sec. 4.2 of the paper;
+// the paper leaves the initialisation open, the chain is this library's choice).
+//
+// Step j keeps, per point, the fp64 squared distance D_i to the nearest of the j centres chosen so
+// far, draws r = u_j * sum(D) with u_j from SplitMix64, and takes the first point whose running
+// prefix of D exceeds r.  Distances use the direct form sum_l (x_l - c_l)^2 in fp64, ascending l,
+// with separately rounded multiply and add.  Sums are hierarchical (thread -> wave -> block ->
+// blocks) in a fixed order, so a chain is reproducible run to run.
+#include "rls_internal.h"
+
+namespace rls {
+
+namespace {
+
+__device__ inline uint64_t splitmix64(uint64_t seed, uint64_t j)
+{
+    uint64_t z = seed + (j + 1) * 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+__device__ inline double uniform01(uint64_t seed, uint64_t j)
+{
+    return (double)(splitmix64(seed, j) >> 11) * 0x1.0p-53;
+}
+
+struct SeedList {
+    uint64_t seed[64];
+};
+
+__global__ void seed_first_kernel(SeedList seeds, int b0, int64_t N, int64_t *chain, int64_t chain_batch_stride)
+{
+    const int b = b0 + blockIdx.x;
+    if (threadIdx.x != 0) return;
+    int64_t first = (int64_t)(uniform01(seeds.seed[blockIdx.x], 0) * (double)N);
+    if (first >= N) first = N - 1;
+    chain[(int64_t)b * chain_batch_stride] = first;
+}
+
+// inclusive scan / sum over a 1024-thread block in fixed order; `tmp` holds 17 doubles
+__device__ inline double wave_inclusive_scan(double v)
+{
+    const int lane = threadIdx.x & 63;
+    for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(v, off, 64);
+        if (lane >= off) v = __dadd_rn(v, o);
+    }
+    return v;
+}
+
+// D_i <- min(D_i, |x_i - c|^2) for the newest centre, plus one sum per block of kSeedBlock points
+__global__ void __launch_bounds__(256) seed_update_kernel(const float *__restrict__ X, int64_t N, int d, int64_t ldx,
+                                                         int64_t x_batch_stride, const int64_t *__restrict__ chain,
+                                                         int64_t chain_batch_stride, int j, double *__restrict__ mind,
+                                                         int64_t mind_batch_stride, double *__restrict__ bsum,
+                                                         int64_t bsum_batch_stride)
+{
+    __shared__ float cs[RLS_MAX_D];
+    __shared__ double wsum[4];
+    const int b = blockIdx.y;
+    const float *Xb = X + (int64_t)b * x_batch_stride;
+    double *D = mind + (int64_t)b * mind_batch_stride;
+    const int64_t centre = chain[(int64_t)b * chain_batch_stride + (j - 1)];
+    if (threadIdx.x < d) cs[threadIdx.x] = Xb[centre * ldx + threadIdx.x];
+    __syncthreads();
+    double local = 0.0;
+    const int64_t base = (int64_t)blockIdx.x * kSeedBlock;
+    for (int i = 0; i < kSeedBlock / 256; ++i) {
+        const int64_t p = base + threadIdx.x + 256 * i;
+        if (p < N) {
+            const float *x = Xb + p * ldx;
+            double acc = 0.0;
+            for (int l = 0; l < d; ++l) {
+                const double diff = __dsub_rn((double)x[l], (double)cs[l]);
+                acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+            }
+            double cur = acc;
+            if (j > 1) {
+                const double old = D[p];
+                cur = acc < old ? acc : old;
+            }
+            D[p] = cur;
+            local = __dadd_rn(local, cur);
+        }
+    }
+    // block sum in fixed order: wave butterfly-free reduction via scan's last lane, then 4 waves in order
+    const double incl = wave_inclusive_scan(local);
+    if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        bsum[(int64_t)b * bsum_batch_stride + blockIdx.x] = __dadd_rn(__dadd_rn(wsum[0], wsum[1]), __dadd_rn(wsum[2], wsum[3]));
+}
+
+// one workgroup per space: total, draw, locate the block, locate the point
+__global__ void __launch_bounds__(1024) seed_pick_kernel(SeedList seeds, int b0, int64_t N, int j, int seed_blocks,
+                                                        const double *__restrict__ mind, int64_t mind_batch_stride,
+                                                        const double *__restrict__ bsum, int64_t bsum_batch_stride,
+                                                        int64_t *chain, int64_t chain_batch_stride)
+{
+    __shared__ double wtot[16];
+    __shared__ double s_prefix_before;   // prefix of all blocks before the chosen block
+    __shared__ int s_block;
+    __shared__ int s_pick;
+    __shared__ double s_total;
+    const int b = b0 + blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double *BS = bsum + (int64_t)b * bsum_batch_stride;
+    const double *D = mind + (int64_t)b * mind_batch_stride;
+    int64_t *ch = chain + (int64_t)b * chain_batch_stride;
+
+    // segment of blocks per thread
+    const int per = (seed_blocks + 1023) / 1024;
+    const int s0 = min(tid * per, seed_blocks), s1 = min(s0 + per, seed_blocks);
+    double local = 0.0;
+    for (int s = s0; s < s1; ++s) local = __dadd_rn(local, BS[s]);
+    double incl = wave_inclusive_scan(local);
+    if (lane == 63) wtot[wave] = incl;
+    if (tid == 0) { s_block = 0x7fffffff; s_pick = 0x7fffffff; }
+    __syncthreads();
+    double wbase = 0.0;
+    for (int w = 0; w < wave; ++w) wbase = __dadd_rn(wbase, wtot[w]);
+    if (tid == 1023) s_total = __dadd_rn(wbase, incl);
+    __syncthreads();
+    const double S = s_total;
+    if (!(S > 0.0)) {
+        // every point coincides with a chosen centre: smallest index not chosen yet
+        if (tid == 0) {
+            int64_t pick = -1;
+            for (int64_t i = 0; i < N && pick < 0; ++i) {
+                bool taken = false;
+                for (int m = 0; m < j; ++m) taken |= (ch[m] == i);
+                if (!taken) pick = i;
+            }
+            ch[j] = pick;
+        }
+        return;
+    }
+    const double r = __dmul_rn(uniform01(seeds.seed[blockIdx.x], (uint64_t)j), S);
+    // first block whose inclusive prefix exceeds r
+    {
+        double run = __dadd_rn(wbase, __dadd_rn(incl, -local));   // exclusive prefix of this thread's segment
+        for (int s = s0; s < s1; ++s) {
+            const double nxt = __dadd_rn(run, BS[s]);
+            if (nxt > r && BS[s] > 0.0) { atomicMin(&s_block, s); break; }
+            run = nxt;
+        }
+    }
+    __syncthreads();
+    int blk = s_block;
+    const bool overflow = (blk == 0x7fffffff);   // r rounded up to S: take the last point with D > 0
+    if (overflow) {
+        __syncthreads();
+        if (tid == 0) s_block = -1;
+        __syncthreads();
+        for (int s = s0; s < s1; ++s)
+            if (BS[s] > 0.0) atomicMax(&s_block, s);
+        __syncthreads();
+        blk = s_block;
+    }
+    // exclusive prefix of the chosen block, recomputed in the same order by the thread that owns it
+    if (blk >= s0 && blk < s1) {
+        double run = __dadd_rn(wbase, __dadd_rn(incl, -local));
+        for (int s = s0; s < blk; ++s) run = __dadd_rn(run, BS[s]);
+        s_prefix_before = run;
+    }
+    __syncthreads();
+    const double before = s_prefix_before;
+    const int64_t p = (int64_t)blk * kSeedBlock + tid;
+    const double v = p < N ? D[p] : 0.0;
+    const double in_wave = wave_inclusive_scan(v);
+    __syncthreads();
+    if (lane == 63) wtot[wave] = in_wave;
+    __syncthreads();
+    double wb = before;
+    for (int w = 0; w < wave; ++w) wb = __dadd_rn(wb, wtot[w]);
+    const double prefix = __dadd_rn(wb, in_wave);
+    if (!overflow) {
+        if (v > 0.0 && prefix > r) atomicMin(&s_pick, tid);
+        __syncthreads();
+        if (s_pick == 0x7fffffff) {   // block-level and point-level rounding disagree: last positive point of the block
+            __syncthreads();
+            if (tid == 0) s_pick = -1;
+            __syncthreads();
+            if (v > 0.0) atomicMax(&s_pick, tid);
+        }
+    } else {
+        __syncthreads();
+        if (tid == 0) s_pick = -1;
+        __syncthreads();
+        if (v > 0.0) atomicMax(&s_pick, tid);
+    }
+    __syncthreads();
+    if (tid == 0) ch[j] = (int64_t)blk * kSeedBlock + s_pick;
+}
+
+}  // namespace
+
+hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
+                             int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
+                             double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,
+                             int32_t seed_blocks, hipStream_t s)
+{
+    for (int b0 = 0; b0 < batch; b0 += 64) {
+        const int nb = batch - b0 < 64 ? batch - b0 : 64;
+        SeedList sl;
+        for (int i = 0; i < 64; ++i) sl.seed[i] = seeds_host[b0 + (i < nb ? i : 0)];
+        hipLaunchKernelGGL(seed_first_kernel, dim3(nb), dim3(64), 0, s, sl, b0, N, chain, chain_batch_stride);
+        for (int j = 1; j < k_max; ++j) {
+            hipLaunchKernelGGL(seed_update_kernel, dim3(seed_blocks, nb), dim3(256), 0, s,
+                               X + (int64_t)b0 * x_batch_stride, N, (int)d, ldx, x_batch_stride,
+                               chain + (int64_t)b0 * chain_batch_stride, chain_batch_stride, j,
+                               mind + (int64_t)b0 * mind_batch_stride, mind_batch_stride,
+                               bsum + (int64_t)b0 * bsum_batch_stride, bsum_batch_stride);
+            hipLaunchKernelGGL(seed_pick_kernel, dim3(nb), dim3(1024), 0, s, sl, b0, N, j, (int)seed_blocks, mind,
+                               mind_batch_stride, bsum, bsum_batch_stride, chain, chain_batch_stride);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace rls

@@ -1,0 +1,211 @@
+// Host entry points of the C ABI declared in rls.h: argument checks, workspace carving, launches.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "rls_internal.h"
+
+namespace rls {
+
+static thread_local hipError_t g_last_hip = hipSuccess;
+void set_hip_error(hipError_t e) { g_last_hip = e; }
+
+static int32_t check_matrix(const float *X, int64_t N, int32_t d, int64_t ldx)
+{
+    if (!X) return RLS_ERR_NULL;
+    if (N < 1 || N > RLS_MAX_N || d < 1 || d > RLS_MAX_D) return RLS_ERR_INVALID_ARG;
+    if (ldx < d) return RLS_ERR_SHAPE;
+    return RLS_OK;
+}
+
+static int32_t check_forest(const rls_forest *f, int32_t d)
+{
+    if (!f) return RLS_ERR_NULL;
+    if (!f->feat_dev || !f->thr_dev || !f->leaf_dev) return RLS_ERR_NULL;
+    if (f->n_trees < 1 || f->depth < 1 || f->depth > RLS_MAX_DEPTH) return RLS_ERR_INVALID_ARG;
+    if (f->n_features != d) return RLS_ERR_SHAPE;
+    return RLS_OK;
+}
+
+static int32_t check_sweep(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch)
+{
+    if (N < 1 || N > RLS_MAX_N || d < 1 || d > RLS_MAX_D) return RLS_ERR_INVALID_ARG;
+    if (k_min < 1 || k_max < k_min || k_max > RLS_MAX_K || (int64_t)k_max > N) return RLS_ERR_INVALID_ARG;
+    if (batch < 1 || batch > RLS_MAX_BATCH) return RLS_ERR_INVALID_ARG;
+    return RLS_OK;
+}
+
+}  // namespace rls
+
+using namespace rls;
+
+extern "C" {
+
+int32_t rls_version(void) { return 100; }
+
+const char *rls_error_string(int32_t code)
+{
+    switch (code) {
+    case RLS_OK: return "ok";
+    case RLS_ERR_INVALID_ARG: return "invalid argument (size, range or limit)";
+    case RLS_ERR_NULL: return "required pointer is null";
+    case RLS_ERR_SHAPE: return "shapes disagree";
+    case RLS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RLS_ERR_HIP: return "HIP runtime error";
+    case RLS_ERR_NOT_IMPLEMENTED: return "not implemented";
+    default: return "unknown error code";
+    }
+}
+
+int32_t rls_last_hip_error(void) { return (int32_t)g_last_hip; }
+
+int32_t rls_gbt_score_batched(const rls_forest *forests, int32_t batch, const float *X_dev, int64_t N, int32_t d,
+                              int64_t ldx, int64_t x_batch_stride, float *score_dev, void *stream)
+{
+    if (!forests || !score_dev) return RLS_ERR_NULL;
+    if (batch < 1 || batch > RLS_MAX_BATCH) return RLS_ERR_INVALID_ARG;
+    int32_t rc = check_matrix(X_dev, N, d, ldx);
+    if (rc != RLS_OK) return rc;
+    if (batch > 1 && x_batch_stride < N * ldx - (ldx - d)) return RLS_ERR_SHAPE;
+    std::vector<ForestArgs> fa((size_t)batch);
+    for (int32_t b = 0; b < batch; ++b) {
+        rc = check_forest(&forests[b], d);
+        if (rc != RLS_OK) return rc;
+        fa[b] = ForestArgs{forests[b].n_trees, forests[b].depth, forests[b].base, forests[b].feat_dev,
+                           forests[b].thr_dev, forests[b].leaf_dev};
+    }
+    RLS_HIP_TRY(launch_gbt_score(fa.data(), batch, X_dev, N, d, ldx, x_batch_stride, score_dev, (hipStream_t)stream));
+    return RLS_OK;
+}
+
+int32_t rls_gbt_score(const rls_forest *forest, const float *X_dev, int64_t N, int32_t d, int64_t ldx,
+                      float *score_dev, void *stream)
+{
+    return rls_gbt_score_batched(forest, 1, X_dev, N, d, ldx, 0, score_dev, stream);
+}
+
+int64_t rls_kmeans_sweep_workspace_bytes(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch)
+{
+    const int32_t rc = check_sweep(N, d, k_min, k_max, batch);
+    if (rc != RLS_OK) return rc;
+    SweepPlan plan;
+    const int32_t prc = make_sweep_plan(N, d, k_min, k_max, &plan);
+    if (prc != RLS_OK) return prc;
+    SweepLayout L;
+    sweep_layout(plan, N, d, k_max, batch, &L);
+    return L.total;
+}
+
+int32_t rls_kmeanspp_chain(const float *X_dev, int64_t N, int32_t d, int64_t ldx, int32_t k_max, uint64_t seed,
+                           int64_t *init_idx_dev, void *workspace_dev, int64_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_matrix(X_dev, N, d, ldx);
+    if (rc != RLS_OK) return rc;
+    if (!init_idx_dev) return RLS_ERR_NULL;
+    rc = check_sweep(N, d, k_max, k_max, 1);
+    if (rc != RLS_OK) return rc;
+    SweepPlan plan;
+    rc = make_sweep_plan(N, d, k_max, k_max, &plan);
+    if (rc != RLS_OK) return rc;
+    SweepLayout L;
+    sweep_layout(plan, N, d, k_max, 1, &L);
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < L.total) return RLS_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace_dev);
+    RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_max, &seed, init_idx_dev, k_max,
+                                  reinterpret_cast<double *>(ws + L.mind), 0, reinterpret_cast<double *>(ws + L.bsum), 0,
+                                  L.seed_blocks, (hipStream_t)stream));
+    return RLS_OK;
+}
+
+int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, int32_t d, int64_t ldx,
+                                 int64_t x_batch_stride, int32_t k_min, int32_t k_max, int32_t iters,
+                                 const uint64_t *seeds, const int64_t *init_idx_dev, int32_t *labels_dev,
+                                 float *centroids_dev, double *inertia_dev, double *inertia_trace_dev,
+                                 int32_t *status_dev, void *workspace_dev, int64_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_matrix(X_dev, N, d, ldx);
+    if (rc != RLS_OK) return rc;
+    rc = check_sweep(N, d, k_min, k_max, batch);
+    if (rc != RLS_OK) return rc;
+    if (!centroids_dev || !inertia_dev || !status_dev) return RLS_ERR_NULL;
+    if (!init_idx_dev && !seeds) return RLS_ERR_NULL;
+    if (iters < 0) return RLS_ERR_INVALID_ARG;
+    if (batch > 1 && x_batch_stride < N * ldx - (ldx - d)) return RLS_ERR_SHAPE;
+    SweepPlan plan;
+    rc = make_sweep_plan(N, d, k_min, k_max, &plan);
+    if (rc != RLS_OK) return rc;
+    SweepLayout L;
+    sweep_layout(plan, N, d, k_max, batch, &L);
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < L.total) return RLS_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace_dev);
+    hipStream_t s = (hipStream_t)stream;
+
+    const int64_t *init = init_idx_dev;
+    int64_t init_bs = k_max;
+    if (!init) {
+        int64_t *chain = reinterpret_cast<int64_t *>(ws + L.chain);
+        RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, x_batch_stride, batch, k_max, seeds, chain, L.per_batch / 8,
+                                      reinterpret_cast<double *>(ws + L.mind), L.per_batch / 8,
+                                      reinterpret_cast<double *>(ws + L.bsum), L.per_batch / 8, L.seed_blocks, s));
+        init = chain;
+        init_bs = L.per_batch / 8;
+    }
+    SweepArgs a;
+    a.X = X_dev; a.N = N; a.d = d; a.ldx = ldx; a.x_batch_stride = x_batch_stride; a.batch = batch; a.iters = iters;
+    a.init_idx = init; a.init_batch_stride = init_bs;
+    a.labels = labels_dev; a.centroids = centroids_dev; a.inertia = inertia_dev; a.trace = inertia_trace_dev;
+    a.status = status_dev; a.ws = ws;
+    RLS_HIP_TRY(launch_sweep(plan, L, a, s));
+    return RLS_OK;
+}
+
+int32_t rls_kmeans_sweep(const float *X_dev, int64_t N, int32_t d, int64_t ldx, int32_t k_min, int32_t k_max,
+                         int32_t iters, uint64_t seed, const int64_t *init_idx_dev, int32_t *labels_dev,
+                         float *centroids_dev, double *inertia_dev, double *inertia_trace_dev, int32_t *status_dev,
+                         void *workspace_dev, int64_t workspace_bytes, void *stream)
+{
+    return rls_kmeans_sweep_batched(1, X_dev, N, d, ldx, 0, k_min, k_max, iters, &seed, init_idx_dev, labels_dev,
+                                    centroids_dev, inertia_dev, inertia_trace_dev, status_dev, workspace_dev,
+                                    workspace_bytes, stream);
+}
+
+int32_t rls_pick_knee(const double *inertia_host, int32_t k_min, int32_t k_max, double knee_const, int32_t *k_out)
+{
+    if (!inertia_host || !k_out) return RLS_ERR_NULL;
+    if (k_min < 1 || k_max < k_min) return RLS_ERR_INVALID_ARG;
+    double previous_loss = INFINITY;
+    int32_t chosen = k_max;
+    for (int32_t k = k_min; k <= k_max; ++k) {
+        const double loss = inertia_host[k - k_min];
+        if (knee_const * loss > previous_loss) { chosen = k; break; }
+        previous_loss = loss;
+    }
+    *k_out = chosen;
+    return RLS_OK;
+}
+
+int32_t rls_snap_to_valid_batched(int32_t batch, const float *centroids_dev, int32_t k, int32_t d, int64_t ldc,
+                                  int64_t c_batch_stride, const rls_knob_domains *domains, int32_t *cfg_dev, void *stream)
+{
+    if (!centroids_dev || !domains || !cfg_dev) return RLS_ERR_NULL;
+    if (batch < 1 || batch > RLS_MAX_BATCH || k < 1 || d < 1 || d > RLS_MAX_D) return RLS_ERR_INVALID_ARG;
+    if (ldc < d) return RLS_ERR_SHAPE;
+    std::vector<DomainArgs> da((size_t)batch);
+    for (int32_t b = 0; b < batch; ++b) {
+        if (!domains[b].offsets_dev || !domains[b].values_dev) return RLS_ERR_NULL;
+        if (domains[b].n_knobs < 1 || domains[b].n_knobs > d) return RLS_ERR_SHAPE;
+        if (domains[b].n_knobs != domains[0].n_knobs) return RLS_ERR_SHAPE;
+        da[b] = DomainArgs{domains[b].n_knobs, domains[b].offsets_dev, domains[b].values_dev};
+    }
+    RLS_HIP_TRY(launch_snap(da.data(), batch, centroids_dev, k, d, ldc, c_batch_stride, cfg_dev, (hipStream_t)stream));
+    return RLS_OK;
+}
+
+int32_t rls_snap_to_valid(const float *centroids_dev, int32_t k, int32_t d, int64_t ldc,
+                          const rls_knob_domains *domains, int32_t *cfg_dev, void *stream)
+{
+    return rls_snap_to_valid_batched(1, centroids_dev, k, d, ldc, 0, domains, cfg_dev, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,139 @@
+// Internal declarations shared by the host entry points and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rls.h"
+
+namespace rls {
+
+// last failing hipError_t on this thread
+void set_hip_error(hipError_t e);
+
+#define RLS_HIP_TRY(expr)                      \
+    do {                                       \
+        hipError_t rls_e_ = (expr);            \
+        if (rls_e_ != hipSuccess) {            \
+            ::rls::set_hip_error(rls_e_);      \
+            return RLS_ERR_HIP;                \
+        }                                      \
+    } while (0)
+
+inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------------------------
+// Sweep plan: how the runs (one per k) of a sweep are packed into workgroup-sized groups.
+//
+// An MFMA tile has 32 centroid rows = 8 quads of 4 rows.  Quad `slot` (0..7) of every tile of a
+// group belongs to one run for the whole group, so the running (best, second best) of a point
+// never leaves its lane.  A group holds R = 8 / S runs, each owning S slots.
+// Centroid j of run r sits in tile (j/4)/S, slot r*S + (j/4)%S, row-in-quad j%4.
+struct GroupDesc {
+    int16_t run0;      // index of the first run (k = k_min + run0)
+    int16_t n_runs;    // real runs in this group (<= 8 / S)
+    int16_t S;         // slots per run: 1, 2, 4 or 8
+    int16_t n_tiles;   // 32-row tiles
+    int32_t tile0;     // tiles of all earlier groups (offset of this group's operand block)
+};
+
+constexpr int kMaxGroups = 128;
+
+struct SweepPlan {
+    int32_t n_groups;
+    int32_t n_runs;      // k_max - k_min + 1
+    int32_t k_min;
+    int32_t total_tiles;
+    int32_t total_rows;  // sum of k over the runs
+    int32_t n_chunks;    // point chunks per group
+    int32_t chunk_len;   // points per chunk (multiple of the tile size)
+    int32_t dp;          // padded feature count: 8, 16 or 32
+    GroupDesc g[kMaxGroups];
+};
+
+// rows of runs k_min .. k_min+run-1
+__host__ __device__ inline int32_t rows_before(int32_t k_min, int32_t run) {
+    return run * k_min + run * (run - 1) / 2;
+}
+
+struct LloydGeometry {
+    int threads;      // workgroup size
+    int tile_points;  // points per tile
+    int lds_budget;   // bytes of LDS one workgroup may use
+};
+LloydGeometry lloyd_geometry(int dp);
+int padded_d(int d);
+// LDS bytes of a group: fixed part + operand tiles + exact-sum accumulators
+int64_t lloyd_group_lds_bytes(int dp, int tile_points, int n_tiles, int real_rows);
+int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan);
+
+// Workspace carving for one sweep (all offsets in bytes from the workspace base, per batch element
+// unless noted).  Filled by sweep_layout().
+struct SweepLayout {
+    int64_t colstat_part;   // per-block partial column statistics
+    int64_t colinfo;        // mean[32] fp32, shift[32] int32, wide[33] int32
+    int64_t chain;          // int64 [k_max] seeding chain
+    int64_t mind;           // fp64 [N] squared distance to the nearest chosen centre
+    int64_t bsum;           // fp64 [seed blocks] block sums of mind
+    int64_t opA;            // fp32 [total_tiles * 32 * dp] centred, -2-scaled centroids in MFMA operand order
+    int64_t cn;             // fp32 [total_tiles * 32] squared norms of the centred centroids (padding: huge)
+    int64_t cnmax;          // fp32 [n_runs] per-run maximum of cn
+    int64_t psum;           // int64 [n_chunks][total_rows][d] partial fixed-point sums
+    int64_t pcnt;           // int32 [n_chunks][total_rows] partial counts
+    int64_t pj;             // fp64 [n_chunks][n_runs] partial losses
+    int64_t losum;          // int64 [total_rows][d] low-order fixed-point sums of wide columns
+    int64_t per_batch;      // bytes per batch element (multiple of 256)
+    int64_t total;          // per_batch * batch
+    int32_t seed_blocks;
+    int32_t stat_blocks;
+};
+void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, int32_t batch, SweepLayout *L);
+
+constexpr int kSeedBlock = 1024;   // points per block of the seeding kernels
+constexpr int kStatBlocks = 256;   // blocks of the column-statistics kernel
+
+// ---------------------------------------------------------------------------------------------
+// kernel launchers (each enqueues on `s` and returns a HIP status)
+struct ForestArgs {
+    int32_t n_trees, depth;
+    float base;
+    const int32_t *feat;
+    const float *thr;
+    const float *leaf;
+};
+hipError_t launch_gbt_score(const ForestArgs *forests_host, int32_t batch, const float *X, int64_t N, int32_t d,
+                            int64_t ldx, int64_t x_batch_stride, float *score, hipStream_t s);
+
+struct DomainArgs {
+    int32_t n_knobs;
+    const int32_t *offsets;
+    const float *values;
+};
+hipError_t launch_snap(const DomainArgs *domains_host, int32_t batch, const float *C, int32_t k, int32_t d, int64_t ldc,
+                       int64_t c_batch_stride, int32_t *cfg, hipStream_t s);
+
+hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
+                             int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
+                             double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,
+                             int32_t seed_blocks, hipStream_t s);
+
+struct SweepArgs {
+    const float *X;
+    int64_t N;
+    int32_t d;
+    int64_t ldx;
+    int64_t x_batch_stride;
+    int32_t batch;
+    int32_t iters;
+    const int64_t *init_idx;      // [batch][k_max]
+    int64_t init_batch_stride;
+    int32_t *labels;              // [batch][n_runs][N] or null
+    float *centroids;             // [batch][total_rows * d]
+    double *inertia;              // [batch][n_runs]
+    double *trace;                // [batch][n_runs][iters+1] or null
+    int32_t *status;              // [batch]
+    char *ws;                     // workspace base
+};
+hipError_t launch_sweep(const SweepPlan &plan, const SweepLayout &L, const SweepArgs &a, hipStream_t s);
+
+}  // namespace rls
