@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the adaptive-sampling hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic trajectory already resident in HBM:
+tree-ensemble scoring of every configuration, the k-means++ chain, the Lloyd sweep over all k
+(assign + update rounds and the final assignment with labels and inertia), the knee pick on the host
+and the snap of the chosen centroids.  The headline value is config-iterations per second:
+N x (number of k) x (Lloyd rounds) per step divided by the step time.
+
+Prints ONE JSON line.  `roofline` describes the dominant kernel (the fused assign + update Lloyd step),
+timed with HIP events recorded by the library on the launch stream during the timed steps;
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="whole_layer", choices=["tiny", "mid", "whole_layer", "large", "batched"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1905_12799_amd import binding as rls
+    from paper_1905_12799_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    rls.lib()   # fails loudly when the HIP library is not built
+
+    w = synth.WORKLOADS[args.workload]
+    batched = w.batch > 1
+    if batched:
+        probs = synth.make_batched_problems(w)
+        X_host = np.stack([p.X for p in probs])
+    else:
+        probs = [synth.make_problem(w)]
+        X_host = probs[0].X
+    X = torch.as_tensor(X_host).cuda()
+    forests = [rls.DeviceForest.from_host(p.forest) for p in probs]
+    domains = [rls.DeviceDomains(p.dom_offsets, p.dom_values) for p in probs]
+    B = w.batch
+    n_k = w.k_max - w.k_min + 1
+    ws_bytes = rls.kmeans_sweep_workspace_bytes(w.N, w.d, w.k_min, w.k_max, B)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    scores = torch.empty((B, w.N) if batched else (w.N,), dtype=torch.float32, device="cuda")
+    seeds = [w.seed + b for b in range(B)]
+    knee_const = 1.05
+    want_labels = not args.no_labels
+
+    ev = {name: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for name in ("score", "sweep", "snap")}
+    stage_ms = {name: 0.0 for name in ev}
+
+    def step(record: bool):
+        ev["score"][0].record()
+        if batched:
+            rls.gbt_score_batched(forests, X, out=scores)
+        else:
+            rls.gbt_score(forests[0], X, out=scores)
+        ev["score"][1].record()
+        ev["sweep"][0].record()
+        if batched:
+            res = rls.kmeans_sweep_batched(X, w.k_min, w.k_max, w.iters, seeds=seeds, want_labels=want_labels,
+                                           workspace=ws, check_status=False)
+        else:
+            res = rls.kmeans_sweep(X, w.k_min, w.k_max, w.iters, seed=seeds[0], want_labels=want_labels,
+                                   workspace=ws, check_status=False)
+        ev["sweep"][1].record()
+        inertia = res.inertia.cpu()            # the knee pick is a host step: one small copy, one sync
+        status = res.status.cpu()
+        if bool((status != 0).any()):
+            raise RuntimeError(f"sweep status {status.tolist()}")
+        ev["snap"][0].record()
+        chosen = []
+        if batched:
+            # one k per space; snap each space's chosen centroids (same k needed for a batched call, so loop)
+            for b in range(B):
+                k = rls.pick_knee(inertia[b].tolist(), w.k_min, w.k_max, knee_const)
+                chosen.append(k)
+                rls.snap_to_valid(res.centroids_of(k, b), domains[b])
+        else:
+            k = rls.pick_knee(inertia.tolist(), w.k_min, w.k_max, knee_const)
+            chosen.append(k)
+            rls.snap_to_valid(res.centroids_of(k), domains[0])
+        ev["snap"][1].record()
+        if record:
+            torch.cuda.synchronize()
+            for name in ev:
+                stage_ms[name] += ev[name][0].elapsed_time(ev[name][1])
+        return chosen
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    rls.profile_enable(True)
+    rls.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        chosen = step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_launch, kernel_ms_total = rls.profile_read()
+    rls.profile_enable(False)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    point_iters = float(w.N) * B * n_k * w.iters
+    value = point_iters / (ms_per_step * 1e-3)
+    sweep_ms = stage_ms["sweep"] / args.steps
+    score_ms = stage_ms["score"] / args.steps
+
+    # dominant kernel: the Lloyd step (assign + update for every k in one launch)
+    kernel_ms = kernel_ms_total / max(n_launch, 1)
+    sum_k = sum(range(w.k_min, w.k_max + 1))
+    alg_bytes = 4.0 * w.d * w.N * B * n_k                 # 4*d bytes per point and (k, round)
+    alg_flops = 2.0 * w.d * sum_k * w.N * B               # 2*d*k flops per point and (k, round)
+    gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    tflops = alg_flops / (kernel_ms * 1e-3) / 1e12
+    hbm_time, mfma_time = alg_bytes / (HBM_PEAK_GBS * 1e9), alg_flops / (MFMA_F32_PEAK_TFLOPS * 1e12)
+    if hbm_time >= mfma_time:
+        roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                    "traffic": None}
+    else:
+        roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+    roofline.update({"kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_ms,
+                     "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+                     "algorithmic_TFLOPs": tflops, "mfma_f32_frac": tflops / MFMA_F32_PEAK_TFLOPS})
+
+    out = {
+        "metric": "config_iter_per_s", "value": value, "unit": "config*iter/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} d={w.d} batch={B} k={w.k_min}..{w.k_max} iters={w.iters} "
+                               f"forest={w.n_trees}x{w.depth}", "labels_written": want_labels,
+                   "knee_const": knee_const, "chosen_k": chosen[:4]},
+        "configs_scored_per_s": float(w.N) * B / (score_ms * 1e-3),
+        "sweep_config_iter_per_s": point_iters / (sweep_ms * 1e-3),
+        "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / args.steps},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        p0 = probs[0]
+        ks = [k for k in (8, 32, 64, 128) if w.k_min <= k <= w.k_max] or [w.k_max]
+        iters_s = 3
+        chain = oracle.kmeanspp_chain(p0.X, max(ks), w.seed)
+        t = time.perf_counter()
+        for k in ks:
+            oracle.lloyd(p0.X, k, iters_s, chain)
+        dt = time.perf_counter() - t
+        n_s = min(w.N, 65536)
+        t = time.perf_counter()
+        oracle.gbt_score(p0.forest, p0.X[:n_s])
+        dt_s = time.perf_counter() - t
+        out["cpu_baseline"] = {
+            "value": float(w.N) * len(ks) * iters_s / dt, "unit": "config*iter/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"Lloyd on the full N={w.N} of one space for k in {ks}, {iters_s} rounds each plus the final "
+                      f"assignment ({dt:.1f} s); tree scoring of the first {n_s} configurations on 1 thread ({dt_s:.1f} s)",
+            "configs_scored_per_s": n_s / dt_s,
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -177,6 +177,16 @@ int32_t rls_snap_to_valid_batched(int32_t batch, const float *centroids_dev, int
                                   int64_t c_batch_stride, const rls_knob_domains *domains, int32_t *cfg_dev,
                                   void *stream);
 
+/*
+ * Timing aid for benchmarks (not part of the paper's method).  While enabled, rls_kmeans_sweep[_batched]
+ * records a pair of HIP events on `stream` around every launch of the Lloyd step kernel (the fused
+ * assign + update pass that dominates Algorithm 1's k-means calls).  rls_profile_read waits for the
+ * recorded events, returns how many launches were timed and their summed duration in milliseconds,
+ * and forgets them.  Not thread-safe; events are created by the library on first use.
+ */
+int32_t rls_profile_enable(int32_t on);
+int32_t rls_profile_read(int32_t *n_launches, double *total_ms);
+
 #ifdef __cplusplus
 }
 #endif

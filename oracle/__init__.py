@@ -55,6 +55,10 @@ def _f32(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
+def threads() -> int:
+    return int(lib().orc_threads())
+
+
 def splitmix64(seed: int, j: int) -> int:
     return int(lib().orc_splitmix64(ctypes.c_uint64(seed), ctypes.c_uint64(j)))
 

@@ -28,6 +28,9 @@
  * Only the loop over points in the assignment step carries an OpenMP pragma.
  */
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -317,6 +320,16 @@ int32_t orc_snap_to_valid(const float *centroids, int32_t k, int32_t d, int64_t 
         }
     }
     return ORC_OK;
+}
+
+/* threads the annotated assignment loop runs on */
+int32_t orc_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
 }
 
 /* two smallest direct-form distances of one point (for the near-tie rule of the parity tests) */

@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.rls_snap_to_valid.argtypes = [vp, i32, i32, i64, ctypes.POINTER(_Domains), vp, vp]
         L.rls_snap_to_valid_batched.restype = i32
         L.rls_snap_to_valid_batched.argtypes = [i32, vp, i32, i32, i64, i64, ctypes.POINTER(_Domains), vp, vp]
+        L.rls_profile_enable.restype = i32
+        L.rls_profile_enable.argtypes = [i32]
+        L.rls_profile_read.restype = i32
+        L.rls_profile_read.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(f64)]
         _lib = L
     return _lib
 
@@ -81,6 +85,17 @@ def version() -> int:
 
 def error_string(code: int) -> str:
     return lib().rls_error_string(ctypes.c_int32(code)).decode()
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().rls_profile_enable(1 if on else 0), "rls_profile_enable")
+
+
+def profile_read():
+    """(launches timed, total milliseconds) of the Lloyd step kernel since the last read."""
+    n, ms = ctypes.c_int32(0), ctypes.c_double(0.0)
+    _check(lib().rls_profile_read(ctypes.byref(n), ctypes.byref(ms)), "rls_profile_read")
+    return int(n.value), float(ms.value)
 
 
 def _stream() -> ctypes.c_void_p:

@@ -28,7 +28,7 @@ def build_library(verbose: bool = False) -> str:
     """Compile every kernel file for gfx950 and link the shared library. Always compiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           "-ffp-contract=off",
+           "-ffp-contract=off", "-mllvm", "-amdgpu-mfma-vgpr-form",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB] + sources()

@@ -2,47 +2,62 @@
 // Algorithm 1 (Sec. 4.2 of the paper), all k side by side, iterations in lock step.
 //
 // Per iteration one launch of lloyd_step_kernel does, for every (group of runs, chunk of points):
-//   phase 0  load a tile of points (raw fp32 into LDS, fixed-point copies into registers)
-//   phase A  distances by fp32 MFMA in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the
-//            column means; per point and run, the best and second-best packed (value, index) keys
+//   phase 0  load a tile of points (raw fp32) into LDS; the next tile's rows travel in registers meanwhile
+//   phase A  distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means, on the
+//            bf16 matrix pipeline: every fp32 operand is split exactly into three bf16 pieces and the six
+//            leading cross products are accumulated in fp32 (fp32-class accuracy; the bf16 pipeline runs
+//            beside the vector ALU, the fp32 one does not); per point and run, the best and second-best
+//            packed (value, index) keys
 //   phase B  points whose two best keys are closer than the error bound of phase A are decided
 //            again in fp64 with the direct form sum_l (x_l - c_l)^2 - the arithmetic that defines
 //            the assignment - so labels do not depend on fp32 cancellation
-//   phase C  exact centroid sums: every member adds its fixed-point row to its cluster's int64
-//            accumulators in LDS (integer adds commute, so the result is independent of order);
-//            per-chunk partials go to global memory and lloyd_centroids_kernel reduces them in 128 bits,
-//            rounds once to fp64, divides by the count and rounds to fp32
+//   phase C  exact centroid sums, kept as running totals: only points whose label differs from the one
+//            of the previous round move their fixed-point row from the old cluster's int64 accumulators
+//            to the new one's (integer adds commute and cancel exactly, so the totals equal a fresh sum
+//            in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel adds them to
+//            the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
 // The final pass replaces phase C by the fp64 loss of every point and the label output.
 #include "rls_internal.h"
 
 namespace rls {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;                // one workgroup per CU: 8 waves, 2 per SIMD
+constexpr int kWaves = kThreads / 64;
 constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding rows: never the minimum
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
+constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by the main accumulator
+constexpr int kLowBits = 36;                  // further bits kept by the low accumulator (wide columns)
 
-__host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 128 : 256; }
+__host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 256 : 512; }
+// MFMA operands: a lane holds 8 bf16 values of its half of the features per K-step (v_mfma_f32_32x32x16_bf16);
+// a 32-row tile stores, per K-step, the three pieces (high, middle, low) of -2c', and then one bias slot.
+__host__ __device__ constexpr int ksteps_of(int dp) { return dp == 32 ? 2 : 1; }
+__host__ __device__ constexpr int tile_slots_of(int dp) { return 3 * ksteps_of(dp) + 1; }          // 16-byte slots per lane
+__host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(dp) * 64 * 16; }    // per 32-row tile
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
 struct Carve {
-    int xs, opA, cn, sums, cnts, labels, queue, misc, total;
+    int xs, opA, cs, sums, cnts, labels, old, queue_b, queue_c, misc, total;
 };
-__host__ __device__ inline Carve carve_lds(int dp, int n_tiles, int real_rows)
+__host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows, bool with_cs)
 {
     const int tp = tile_points_of(dp);
     Carve c;
     int off = 0;
-    c.xs = off;      off += tp * (dp + 4) * 4;
-    c.opA = off;     off += n_tiles * 32 * dp * 4;
-    c.cn = off;      off += n_tiles * 32 * 4;
-    c.sums = off;    off += real_rows * (dp + 1) * 8;
-    c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;
-    c.labels = off;  off += tp * 8;
-    c.queue = off;   off += tp * 8 * 2;
+    c.xs = off;      off += tp * (dp + 4) * 4;                 // raw tile rows, padded stride
+    c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (bf16 pieces + bias)
+    c.cs = off;      off += with_cs ? (real_rows * d * 4 + 15) / 16 * 16 : 0;   // centroids as given (for fp64 distances)
+    c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point delta sums
+    c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
+    c.labels = off;  off += tp * 8;                            // labels of the tile, [point][run]
+    c.old = off;     off += tp * 8;                            // previous labels of queued points
+    c.queue_b = off; off += tp * 8 * 2;                        // (point, run) pairs to decide again in fp64
+    c.queue_c = off; off += tp * 8 * 2;                        // (point, run) pairs whose label changed
     c.misc = off;    off += 1024;
     c.total = off;
     return c;
@@ -61,17 +76,11 @@ struct StepArgs {
     const int32_t *status;   // [batch]
     char *ws;                // workspace base
     int64_t ws_bs;           // bytes per batch element
-    int64_t off_colinfo, off_opA, off_cn, off_cnmax, off_psum, off_pcnt, off_pj, off_losum;
+    int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev;
+    int32_t first_round;     // 1: no point has a label yet (every assignment is a change)
 };
 
-__device__ inline int med3_i32(int a, int b, int c)
-{
-    int r;
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
-// x * 2^shift as an integer; exact whenever x is a multiple of 2^-shift
+// x * 2^shift truncated toward zero; exact whenever x is a multiple of 2^-shift
 __device__ inline long long to_fixed(float x, int shift)
 {
     const unsigned u = __float_as_uint(x);
@@ -92,8 +101,6 @@ __device__ inline long long to_fixed(float x, int shift)
 
 // The part of x below the column grid 2^-shift, scaled by 2^(shift + kLowBits): the bits that to_fixed drops.
 // Non-zero only in columns whose values span more than kGridBits binary digits.
-constexpr int kGridBits = 44;   // bits of |x * 2^shift| kept by the main accumulator
-constexpr int kLowBits = 36;    // further bits kept by the low accumulator
 __device__ inline long long fixed_low(float x, int shift)
 {
     const unsigned u = __float_as_uint(x);
@@ -125,6 +132,20 @@ __device__ inline double sqdist64(const float *x, const float *c, int d)
     return acc;
 }
 
+// v = h + m + l exactly, each piece a bf16 (8 significant bits): h and m by truncation, l is what is left
+__device__ inline void split3(float v, unsigned &h, unsigned &m, unsigned &l)
+{
+    const unsigned b = __float_as_uint(v);
+    h = b >> 16;
+    const float r = v - __uint_as_float(b & 0xffff0000u);
+    const unsigned rb = __float_as_uint(r);
+    m = rb >> 16;
+    const float r2 = r - __uint_as_float(rb & 0xffff0000u);
+    l = __float_as_uint(r2) >> 16;
+}
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
 // The index that phase A packs into the low 7 bits of a key is the centroid index within the run:
 // centroid j lives in tile (j/4)/S, slot (j/4)%S of its run, row j%4 (see GroupDesc).
 template <int S>
@@ -138,78 +159,185 @@ __device__ inline int key_index(int t, int a, int i)
 template <int S>
 __device__ inline int state_of(int a) { return S == 1 ? a : (S == 2 ? (a >> 1) : 0); }
 
-// Phase A for one wave: NB blocks of 32 points against all tiles of the group.
-template <int DP, int S>
-__device__ inline void phase_a(const float *xs, const float *opA_s, const float *cn_s, const float *mu_s,
-                               const float *cnmax_s, unsigned char *labels_s, unsigned short *queue, int *qcount,
-                               int n_tiles, int n_runs_g, int nvalid, float eps_a)
+// (bits & mask) | idx.  The mask is kept opaque to the compiler (a VGPR) so that this selects one and-or
+// instruction with the index as its scalar operand.  It must stay a compiler-visible operation (not inline
+// assembly): it reads MFMA results, and the wait states between an MFMA and the first read of its result
+// are inserted by the compiler.
+__device__ inline int pack_key(float v, int mask, int idx)
 {
+    return (__float_as_int(v) & mask) | idx;
+}
+
+// fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run (best, second best) states
+template <int S, int ST>
+__device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int k0 = pack_key(acc[4 * q + 0], mask, kidx[4 * q + 0]);
+        const int k1 = pack_key(acc[4 * q + 1], mask, kidx[4 * q + 1]);
+        const int k2 = pack_key(acc[4 * q + 2], mask, kidx[4 * q + 2]);
+        const int k3 = pack_key(acc[4 * q + 3], mask, kidx[4 * q + 3]);
+        const int lo01 = min(k0, k1), hi01 = max(k0, k1), lo23 = min(k2, k3), hi23 = max(k2, k3);
+        const int lo = min(lo01, lo23);
+        const int sec = min(min(max(lo01, lo23), hi01), hi23);        // second smallest of the four
+        const int st = state_of<S>(q);
+        m2[st] = min(min(max(m1[st], lo), m2[st]), sec);
+        m1[st] = min(m1[st], lo);
+    }
+}
+
+// Phase A for one wave: NB blocks of 32 points against all tiles of the group.
+// The MFMA contracts over the d centred features plus one extra pair (1, |c'|^2) x (|x'|^2, 1), so the
+// accumulator holds |x'|^2 + |c'|^2 - 2 x'.c' directly and starts from zero.  The results of one tile block
+// are folded into the running minima while the matrix unit works on the next block.
+// what phase A needs besides the tile
+struct PhaseACtx {
+    const float *xs, *mu_s, *cnmax_s;
+    const uint4 *opA_s;
+    unsigned char *labels_s, *old_s;
+    unsigned short *queue_b, *queue_c;
+    int *qcount_b, *qcount_c;
+    unsigned char *prev_tile;     // global: previous labels, prev_tile[rl * prev_stride + p]; null when not tracked
+    int64_t prev_stride;
+    int n_tiles, n_runs_g, nvalid;
+    float eps_a;
+};
+
+template <int DP, int S>
+__device__ inline void phase_a(const PhaseACtx &c)
+{
+    const float *xs = c.xs, *mu_s = c.mu_s;
+    const uint4 *opA_s = c.opA_s;
+    const int n_tiles = c.n_tiles;
     constexpr int TP = tile_points_of(DP);
-    constexpr int NB = TP / 128;
+    constexpr int NB = TP / (32 * kWaves);
     constexpr int H = DP / 2;                       // features per half-wave
+    constexpr int NK = ksteps_of(DP);               // K-steps of 16 per cross term
+    constexpr int NS = tile_slots_of(DP);           // operand slots per tile and lane
+    constexpr int HP = 8 * NK;                      // feature slots per half-wave (H padded to whole K-steps)
     constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);
     constexpr int XS = DP + 4;
+    constexpr int NM = 6 * NK + 1;                  // MFMAs per tile block
+    constexpr int VPER = (56 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hl = lane >> 5;
+    int mask = (int)0xffffff80;
+    asm volatile("" : "+v"(mask));                  // keep the mask in a VGPR
 
-    float mu[H];
-#pragma unroll
-    for (int s = 0; s < H; ++s) mu[s] = mu_s[hl * H + s];
-
-    float b[NB][H];
+    // B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
+    // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
+    bf16x8 bx[NB][3][NK], bb[NB];
     float xn[NB];
     int m1[NB][ST], m2[NB][ST];
+    {
+        float mu[HP];
 #pragma unroll
-    for (int pb = 0; pb < NB; ++pb) {
-        const int p = wave * 32 * NB + pb * 32 + n;
-        const float4 *row = reinterpret_cast<const float4 *>(xs + p * XS + hl * H);
-        float part = 0.0f;
+        for (int s = 0; s < HP; ++s) mu[s] = s < H ? mu_s[hl * H + s] : 0.0f;
 #pragma unroll
-        for (int c4 = 0; c4 < H / 4; ++c4) {
-            const float4 v = row[c4];
-            b[pb][4 * c4 + 0] = v.x - mu[4 * c4 + 0];
-            b[pb][4 * c4 + 1] = v.y - mu[4 * c4 + 1];
-            b[pb][4 * c4 + 2] = v.z - mu[4 * c4 + 2];
-            b[pb][4 * c4 + 3] = v.w - mu[4 * c4 + 3];
+        for (int pb = 0; pb < NB; ++pb) {
+            const int p = wave * 32 * NB + pb * 32 + n;
+            float xc[HP];
+#pragma unroll
+            for (int s = 0; s < HP; ++s) xc[s] = 0.0f;
+            const float4 *row = reinterpret_cast<const float4 *>(xs + p * XS + hl * H);
+#pragma unroll
+            for (int c4 = 0; c4 < H / 4; ++c4) {
+                const float4 v = row[c4];
+                xc[4 * c4 + 0] = v.x - mu[4 * c4 + 0];
+                xc[4 * c4 + 1] = v.y - mu[4 * c4 + 1];
+                xc[4 * c4 + 2] = v.z - mu[4 * c4 + 2];
+                xc[4 * c4 + 3] = v.w - mu[4 * c4 + 3];
+            }
+            float part = 0.0f;
+#pragma unroll
+            for (int s = 0; s < H; ++s) part = fmaf(xc[s], xc[s], part);
+            xn[pb] = part + __shfl_xor(part, 32, 64);
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) {
+                unsigned ph[8], pm[8], pl[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) split3(xc[8 * ks + i], ph[i], pm[i], pl[i]);
+                bx[pb][0][ks] = as_bf16x8(make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
+                bx[pb][1][ks] = as_bf16x8(make_uint4(pm[0] | (pm[1] << 16), pm[2] | (pm[3] << 16), pm[4] | (pm[5] << 16), pm[6] | (pm[7] << 16)));
+                bx[pb][2][ks] = as_bf16x8(make_uint4(pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16), pl[6] | (pl[7] << 16)));
+            }
+            unsigned nh, nm, nl;
+            split3(xn[pb], nh, nm, nl);
+            bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
+#pragma unroll
+            for (int st = 0; st < ST; ++st) { m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; }
         }
-#pragma unroll
-        for (int s = 0; s < H; ++s) part = fmaf(b[pb][s], b[pb][s], part);
-        xn[pb] = part + __shfl_xor(part, 32, 64);
-#pragma unroll
-        for (int st = 0; st < ST; ++st) { m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; }
     }
 
-    for (int t = 0; t < n_tiles; ++t) {
-        float a[H];
+    // labels these (point, run) pairs had in the previous round (loads complete while the tiles are processed)
+    unsigned char oldl[NB][ST];
 #pragma unroll
-        for (int c4 = 0; c4 < H / 4; ++c4) {
-            const float4 v = *reinterpret_cast<const float4 *>(opA_s + ((((t * 2 + hl) * (H / 4) + c4) * 32 + n) << 2));
-            a[4 * c4 + 0] = v.x; a[4 * c4 + 1] = v.y; a[4 * c4 + 2] = v.z; a[4 * c4 + 3] = v.w;
+    for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+        for (int st = 0; st < ST; ++st) {
+            const int p = wave * 32 * NB + pb * 32 + n;
+            const int rl = S == 8 ? 0 : hl * ST + st;
+            oldl[pb][st] = (c.prev_tile && rl < c.n_runs_g && p < c.nvalid) ? c.prev_tile[rl * c.prev_stride + p] : (unsigned char)0xff;
         }
-        floatx16 cnv;
+
+    // operand slots of tile t for this lane: pieces (high, middle, low) of -2c' per K-step, then the bias slot
+    bf16x8 a_cur[NS];
+    auto load_a = [&](bf16x8 (&dst)[NS], int t) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float4 v = *reinterpret_cast<const float4 *>(cn_s + t * 32 + 8 * q + 4 * hl);
-            cnv[4 * q + 0] = v.x; cnv[4 * q + 1] = v.y; cnv[4 * q + 2] = v.z; cnv[4 * q + 3] = v.w;
+        for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
+    };
+    load_a(a_cur, 0);
+
+    // results of the previous tile block, not folded yet; starts as "no result" (keys above every real key)
+    const float big = __int_as_float(kBigKey);
+    floatx16 acc_prev = {big, big, big, big, big, big, big, big, big, big, big, big, big, big, big, big};
+    int kidx_old[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) kidx_old[e] = 0;
+
+    for (int t = 0; t < n_tiles; ++t) {
+        bf16x8 a_nxt[NS];
+        load_a(a_nxt, t + 1 < n_tiles ? t + 1 : t);
+        // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
+        int kidx[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            kidx[e] = key_index<S>(t, e >> 2, e & 3);
+            asm("" : "+s"(kidx[e]));
         }
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            floatx16 acc = cnv;
+            // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
+            floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int s = 0; s < H; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[pb][s], acc, 0, 0, 0);
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // m.m
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[2 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // l.h
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = acc[4 * q + i] + xn[pb];
-                    const int key = (__float_as_int(v) & (int)0xffffff80) | key_index<S>(t, q, i);
-                    const int st = state_of<S>(q);
-                    m2[pb][st] = med3_i32(m1[pb][st], m2[pb][st], key);
-                    m1[pb][st] = min(m1[pb][st], key);
-                }
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][2][ks], acc, 0, 0, 0);   // h.l
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // m.h
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // h.m
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
+            if (pb == 0) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
+            else fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1]);
+#pragma unroll
+            for (int s = 0; s < NM; ++s) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);   // then a share of the fold
             }
+            acc_prev = acc;
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
+#pragma unroll
+        for (int sl = 0; sl < NS; ++sl) a_cur[sl] = a_nxt[sl];
     }
+    fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
 
 #pragma unroll
     for (int pb = 0; pb < NB; ++pb) {
@@ -217,8 +345,8 @@ __device__ inline void phase_a(const float *xs, const float *opA_s, const float 
         if (S == 8) {
             // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
             int k1 = m1[pb][0], k2 = m2[pb][0];
-            if (k1 != kBigKey) k1 |= hl << 4;
-            if (k2 != kBigKey) k2 |= hl << 4;
+            if (k1 < kBigKey) k1 |= hl << 4;
+            if (k2 < kBigKey) k2 |= hl << 4;
             const int o1 = __shfl_xor(k1, 32, 64), o2 = __shfl_xor(k2, 32, 64);
             m1[pb][0] = min(k1, o1);
             m2[pb][0] = min(max(k1, o1), min(k2, o2));
@@ -227,21 +355,28 @@ __device__ inline void phase_a(const float *xs, const float *opA_s, const float 
         for (int st = 0; st < ST; ++st) {
             const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
             const bool writer = (S == 8) ? (hl == 0) : true;
-            if (!writer || rl >= n_runs_g) continue;
+            if (!writer || rl >= c.n_runs_g) continue;
             unsigned char lab = 0xff;
-            if (p < nvalid) {
+            if (p < c.nvalid) {
                 const int k1 = m1[pb][st], k2 = m2[pb][st];
                 lab = (unsigned char)(k1 & 127);
                 const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
                 // error bound of the fp32 expansion (rounding of norms, products and the centring) plus the
                 // 7 mantissa bits given up to the index in each key
-                const float tol = eps_a * (xn[pb] + cnmax_s[rl]) + 6.2e-5f * fabsf(f2) + 1.0e-30f;
+                const float tol = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 6.2e-5f * fabsf(f2) + 1.0e-30f;
                 if (!(f2 - f1 > tol)) {
-                    const int slot = atomicAdd(qcount, 1);
-                    queue[slot] = (unsigned short)(p | (rl << 8));
+                    // too close to call in fp32: phase B decides (and then looks at the previous label)
+                    const int slot = atomicAdd(c.qcount_b, 1);
+                    c.queue_b[slot] = (unsigned short)(p | (rl << 9));
+                    c.old_s[p * 8 + rl] = oldl[pb][st];
+                } else if (c.prev_tile && lab != oldl[pb][st]) {
+                    const int slot = atomicAdd(c.qcount_c, 1);
+                    c.queue_c[slot] = (unsigned short)(p | (rl << 9));
+                    c.old_s[p * 8 + rl] = oldl[pb][st];
+                    c.prev_tile[rl * c.prev_stride + p] = lab;
                 }
             }
-            labels_s[p * 8 + rl] = lab;
+            c.labels_s[p * 8 + rl] = lab;
         }
     }
 }
@@ -253,6 +388,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     constexpr int XS = DP + 4;
     constexpr int PPP = kThreads / DP;            // points per pass of the (point, feature) mapping
     constexpr int NQ = TP / PPP;                  // passes per tile
+    constexpr int TPP = DP / 4;                   // threads per point of the (point, 4 features) mapping
+    constexpr int PPP4 = kThreads / TPP;          // points per pass of that mapping
+    constexpr int NQ4 = TP / PPP4;                // passes per tile
+    constexpr int RSTEP = kThreads / TP;          // runs covered per pass of the (point, run) mapping: 1 or 2
+    constexpr int NR = 8 / RSTEP;                 // passes of the (point, run) mapping
     constexpr bool LOSS = FINAL || TRACE;
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -265,97 +405,138 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     const int k0 = plan.k_min + g.run0;                                   // k of the group's first run
     const int grow0 = rows_before(plan.k_min, g.run0);                    // first centroid row of the group
     const int real_rows = rows_before(plan.k_min, g.run0 + g.n_runs) - grow0;
-    const Carve cv = carve_lds(DP, g.n_tiles, real_rows);
+    const Carve cv = carve_lds(DP, d, g.n_tiles, real_rows, g.cs_lds != 0);
 
     float *xs = reinterpret_cast<float *>(smem + cv.xs);
-    float *opA_s = reinterpret_cast<float *>(smem + cv.opA);
-    float *cn_s = reinterpret_cast<float *>(smem + cv.cn);
+    uint4 *opA_s = reinterpret_cast<uint4 *>(smem + cv.opA);
+    float *cs_lds = reinterpret_cast<float *>(smem + cv.cs);
     unsigned long long *sums = reinterpret_cast<unsigned long long *>(smem + cv.sums);
     int *cnts = reinterpret_cast<int *>(smem + cv.cnts);
     unsigned char *labels_s = smem + cv.labels;
-    unsigned short *queue = reinterpret_cast<unsigned short *>(smem + cv.queue);
+    unsigned char *old_s = smem + cv.old;
+    unsigned short *queue_b = reinterpret_cast<unsigned short *>(smem + cv.queue_b);
+    unsigned short *queue_c = reinterpret_cast<unsigned short *>(smem + cv.queue_c);
     float *mu_s = reinterpret_cast<float *>(smem + cv.misc);              // [32]
     int *shift_s = reinterpret_cast<int *>(smem + cv.misc + 128);         // [32]
-    float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 256);     // [8]
-    int *qcount = reinterpret_cast<int *>(smem + cv.misc + 288);
-    int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 576);         // [32] + any at [32]
-    double *jpart = reinterpret_cast<double *>(smem + cv.misc + 320);     // [8][4]
+    int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
+    float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
+    int *qcount_b = reinterpret_cast<int *>(smem + cv.misc + 432);
+    int *qcount_c = reinterpret_cast<int *>(smem + cv.misc + 436);
+    double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][kWaves]
 
     const int tid = threadIdx.x;
     char *wsb = a.ws + (int64_t)b * a.ws_bs;
     const float *Xb = a.X + (int64_t)b * a.x_bs;
     const float *Cb = a.C + (int64_t)b * a.c_bs;
+    unsigned char *prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev);   // [n_runs][N] labels of the last round
+    const bool first_round = a.first_round != 0;
+    const bool track = !FINAL && !first_round;      // compare with, and update, the previous labels point by point
 
-    // group operands and column info into LDS; accumulators to zero
+    // group operands, centroids and column info into LDS; accumulators to zero
     {
         const float *colmean = reinterpret_cast<const float *>(wsb + a.off_colinfo);
         const int *colshift = reinterpret_cast<const int *>(wsb + a.off_colinfo + 128);
         const int *colwide = reinterpret_cast<const int *>(wsb + a.off_colinfo + 256);
         if (tid < 32) { mu_s[tid] = tid < DP ? colmean[tid] : 0.0f; shift_s[tid] = colshift[tid]; }
         if (tid < 33) wide_s[tid] = colwide[tid];
-        const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(wsb + a.off_opA) + (int64_t)g.tile0 * 32 * DP);
-        float4 *dst = reinterpret_cast<float4 *>(opA_s);
-        for (int e = tid; e < g.n_tiles * 32 * DP / 4; e += kThreads) dst[e] = src[e];
-        const float *cnsrc = reinterpret_cast<const float *>(wsb + a.off_cn) + (int64_t)g.tile0 * 32;
-        for (int e = tid; e < g.n_tiles * 32; e += kThreads) cn_s[e] = cnsrc[e];
+        const uint4 *src = reinterpret_cast<const uint4 *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
+        for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
+        if (g.cs_lds) {
+            const float *csrc = Cb + (int64_t)grow0 * d;
+            for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[e] = csrc[e];
+        }
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
         if (!FINAL) {
             for (int e = tid; e < real_rows * (DP + 1); e += kThreads) sums[e] = 0ull;
             for (int e = tid; e < real_rows; e += kThreads) cnts[e] = 0;
         }
-        if (tid == 0) *qcount = 0;
+        if (tid == 0) { *qcount_b = 0; *qcount_c = 0; }
     }
     __syncthreads();
 
-    const int l = tid % DP, pg = tid / DP;
+    // the group's centroids as given: the LDS copy, or global memory when the copy did not fit
+    const float *cs = g.cs_lds ? cs_lds : Cb + (int64_t)grow0 * d;
+    const int l = tid % DP, pg = tid / DP;                           // (point, feature) mapping
+    const int l4 = (tid % TPP) * 4, pg4 = tid / TPP;                 // (point, 4 features) mapping
     const int my_shift = shift_s[l];
     const bool any_wide = wide_s[32] != 0;
     const bool my_wide = wide_s[l] != 0;
-    const float eps_a = (float)(DP + 16) * 2.384185791015625e-07f;   // (DP + 16) * 2^-22
+    // bound on the error of phase A's distances relative to |x'|^2 + |c'|^2: dropped piece products (2^-23), seven
+    // chained fp32 accumulations of up to 16 products each, rounding of the norms and of the centring
+    const float eps_a = (float)(8 * (DP + 8)) * 1.1920928955078125e-07f;   // 8 (DP + 8) 2^-23
+    const int pr_p = tid % TP;                                       // (point, run) mapping: this thread's point
+    // 16-byte loads need whole quads of features and aligned rows
+    const bool vec_ok = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
 
-    double jloc[8];
+    double jloc[NR];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) jloc[i] = 0.0;
+    for (int i = 0; i < NR; ++i) jloc[i] = 0.0;
 
     const int64_t chunk_begin = (int64_t)chunk * plan.chunk_len;
     const int64_t chunk_end = min(a.N, chunk_begin + plan.chunk_len);
 
+    // raw rows of the next tile travel in registers while the current tile is processed
+    float4 xr[NQ4];
+    auto fetch_tile = [&](int64_t pt) {
+        const int nv = (int)max((int64_t)0, min((int64_t)TP, chunk_end - pt));
+#pragma unroll
+        for (int i = 0; i < NQ4; ++i) {
+            const int p = pg4 + PPP4 * i;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (p < nv) {
+                const float *row = Xb + (pt + p) * a.ldx;
+                if (vec_ok) {
+                    if (l4 < d) v = *reinterpret_cast<const float4 *>(row + l4);
+                } else {
+                    if (l4 + 0 < d) v.x = row[l4 + 0];
+                    if (l4 + 1 < d) v.y = row[l4 + 1];
+                    if (l4 + 2 < d) v.z = row[l4 + 2];
+                    if (l4 + 3 < d) v.w = row[l4 + 3];
+                }
+            }
+            xr[i] = v;
+        }
+    };
+    fetch_tile(chunk_begin);
+
+    PhaseACtx ctx;
+    ctx.xs = xs; ctx.opA_s = opA_s; ctx.mu_s = mu_s; ctx.cnmax_s = cnmax_s;
+    ctx.labels_s = labels_s; ctx.old_s = old_s; ctx.queue_b = queue_b; ctx.queue_c = queue_c;
+    ctx.qcount_b = qcount_b; ctx.qcount_c = qcount_c;
+    ctx.prev_stride = a.N; ctx.n_tiles = g.n_tiles; ctx.n_runs_g = g.n_runs; ctx.eps_a = eps_a;
+
     for (int64_t p0 = chunk_begin; p0 < chunk_end; p0 += TP) {
         const int nvalid = (int)min((int64_t)TP, chunk_end - p0);
-        // ---- phase 0: tile load
-        long long q[NQ];
+        // ---- phase 0: tile into LDS; start the loads of the next tile
 #pragma unroll
-        for (int i = 0; i < NQ; ++i) {
-            const int p = pg + PPP * i;
-            float x = 0.0f;
-            if (p < nvalid && l < d) x = Xb[(p0 + p) * a.ldx + l];
-            xs[p * XS + l] = x;
-            q[i] = to_fixed(x, my_shift);
-        }
+        for (int i = 0; i < NQ4; ++i) *reinterpret_cast<float4 *>(xs + (pg4 + PPP4 * i) * XS + l4) = xr[i];
+        fetch_tile(p0 + TP);
         __syncthreads();
 
-        // ---- phase A
+        // ---- phase A (the lanes that own a (point, run) result also compare it with the previous label)
+        ctx.nvalid = nvalid;
+        ctx.prev_tile = track ? prev + (int64_t)g.run0 * a.N + p0 : nullptr;
         switch (g.S) {
-        case 1: phase_a<DP, 1>(xs, opA_s, cn_s, mu_s, cnmax_s, labels_s, queue, qcount, g.n_tiles, g.n_runs, nvalid, eps_a); break;
-        case 2: phase_a<DP, 2>(xs, opA_s, cn_s, mu_s, cnmax_s, labels_s, queue, qcount, g.n_tiles, g.n_runs, nvalid, eps_a); break;
-        case 4: phase_a<DP, 4>(xs, opA_s, cn_s, mu_s, cnmax_s, labels_s, queue, qcount, g.n_tiles, g.n_runs, nvalid, eps_a); break;
-        default: phase_a<DP, 8>(xs, opA_s, cn_s, mu_s, cnmax_s, labels_s, queue, qcount, g.n_tiles, g.n_runs, nvalid, eps_a); break;
+        case 1: phase_a<DP, 1>(ctx); break;
+        case 2: phase_a<DP, 2>(ctx); break;
+        case 4: phase_a<DP, 4>(ctx); break;
+        default: phase_a<DP, 8>(ctx); break;
         }
         __syncthreads();
 
         // ---- phase B: exact fp64 decision for the queued (point, run) pairs, one pair per wave at a time
         {
-            const int nq = *qcount;
+            const int nq = *qcount_b;
             const int lane = tid & 63, wave = tid >> 6;
-            for (int e = wave; e < nq; e += kThreads / 64) {
-                const int ent = queue[e];
-                const int p = ent & 255, rl = ent >> 8;
+            for (int e = wave; e < nq; e += kWaves) {
+                const int ent = queue_b[e];
+                const int p = ent & 511, rl = ent >> 9;
                 const int k = k0 + rl;
-                const float *crun = Cb + (int64_t)(rows_before(plan.k_min, g.run0 + rl)) * d;
+                const float *crun = cs + (rl * k0 + rl * (rl - 1) / 2) * d;
                 double best = INFINITY;
                 int arg = 0x7fffffff;
                 for (int j = lane; j < k; j += 64) {
-                    const double dist = sqdist64(xs + p * XS, crun + (int64_t)j * d, d);
+                    const double dist = sqdist64(xs + p * XS, crun + j * d, d);
                     if (dist < best) { best = dist; arg = j; }
                 }
 #pragma unroll
@@ -364,45 +545,77 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
                     const int oa = __shfl_xor(arg, off, 64);
                     if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
                 }
-                if (lane == 0) labels_s[p * 8 + rl] = (unsigned char)arg;
-            }
-        }
-        __syncthreads();
-        if (tid == 0) *qcount = 0;
-
-        // ---- phase C: exact sums (integer adds to the cluster's accumulators)
-        if (!FINAL) {
-#pragma unroll
-            for (int i = 0; i < NQ; ++i) {
-                const int p = pg + PPP * i;
-                if (p < nvalid && l < d) {
-                    const uint2 lab8 = *reinterpret_cast<const uint2 *>(labels_s + p * 8);
-                    int rowbase = 0;
-                    for (int rl = 0; rl < g.n_runs; ++rl) {
-                        const unsigned w = rl < 4 ? lab8.x : lab8.y;
-                        const int j = (w >> (8 * (rl & 3))) & 0xff;
-                        const int row = rowbase + j;
-                        atomicAdd(&sums[row * (DP + 1) + l], (unsigned long long)q[i]);
-                        if (l == 0) atomicAdd(&cnts[row], 1);
-                        rowbase += k0 + rl;
+                if (lane == 0) {
+                    labels_s[p * 8 + rl] = (unsigned char)arg;
+                    if (track && arg != (int)old_s[p * 8 + rl]) {
+                        const int slot = atomicAdd(qcount_c, 1);
+                        queue_c[slot] = (unsigned short)ent;
+                        prev[(int64_t)(g.run0 + rl) * a.N + p0 + p] = (unsigned char)arg;
                     }
                 }
             }
-            if (any_wide) {
-                // rare: values with bits below the column grid add those bits to a global integer accumulator
-                long long *losum = reinterpret_cast<long long *>(wsb + a.off_losum);
-#pragma unroll 1
-                for (int i = 0; i < NQ; ++i) {
-                    const int p = pg + PPP * i;
-                    if (p < nvalid && l < d && my_wide) {
-                        const long long lo = fixed_low(xs[p * XS + l], my_shift);
-                        if (lo != 0) {
+        }
+        __syncthreads();
+
+        // ---- phase C: exact sums
+        if (!FINAL) {
+            long long *losum = reinterpret_cast<long long *>(wsb + a.off_losum);
+            if (first_round) {
+                // every point joins a cluster: dense pass, no queue
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    const int rl = tid / TP + RSTEP * i;
+                    if (rl < g.n_runs && pr_p < nvalid) {
+                        const int j = labels_s[pr_p * 8 + rl];
+                        atomicAdd(&cnts[rl * k0 + rl * (rl - 1) / 2 + j], 1);
+                        prev[(int64_t)(g.run0 + rl) * a.N + p0 + pr_p] = (unsigned char)j;
+                    }
+                }
+                if (l < d) {
+                    for (int i = 0; i < NQ; ++i) {
+                        const int p = pg + PPP * i;
+                        if (p < nvalid) {
+                            const float x = xs[p * XS + l];
+                            const unsigned long long q = (unsigned long long)to_fixed(x, my_shift);
+                            const long long lo = (any_wide && my_wide) ? fixed_low(x, my_shift) : 0;
+                            const uint2 lab8 = *reinterpret_cast<const uint2 *>(labels_s + p * 8);
+                            int rowbase = 0;
                             for (int rl = 0; rl < g.n_runs; ++rl) {
-                                const int j = labels_s[p * 8 + rl];
-                                const int crow = rows_before(plan.k_min, g.run0 + rl) + j;
-                                atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(int64_t)crow * d + l]), (unsigned long long)lo);
+                                const unsigned w = rl < 4 ? lab8.x : lab8.y;
+                                const int row = rowbase + (int)((w >> (8 * (rl & 3))) & 0xffu);
+                                atomicAdd(&sums[row * (DP + 1) + l], q);
+                                if (lo != 0) atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(int64_t)(grow0 + row) * d + l]), (unsigned long long)lo);
+                                rowbase += k0 + rl;
                             }
                         }
+                    }
+                }
+            } else {
+                // move the rows of points whose label changed from the old cluster's sums to the new one's
+                const int nq = *qcount_c;
+                for (int e = pg; e < nq; e += PPP) {
+                    const int ent = queue_c[e];
+                    const int p = ent & 511, rl = ent >> 9;
+                    const int ol = old_s[p * 8 + rl], nl = labels_s[p * 8 + rl];
+                    const int rowbase = rl * k0 + rl * (rl - 1) / 2;
+                    if (l < d) {
+                        const float x = xs[p * XS + l];
+                        const long long q = to_fixed(x, my_shift);
+                        if (ol != 0xff) atomicAdd(&sums[(rowbase + ol) * (DP + 1) + l], (unsigned long long)(-q));
+                        atomicAdd(&sums[(rowbase + nl) * (DP + 1) + l], (unsigned long long)q);
+                        if (any_wide && my_wide) {
+                            // rare: bits below the column grid go to a global integer accumulator
+                            const long long lo = fixed_low(x, my_shift);
+                            if (lo != 0) {
+                                const int64_t crow = grow0 + rowbase;
+                                if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(crow + ol) * d + l]), (unsigned long long)(-lo));
+                                atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(crow + nl) * d + l]), (unsigned long long)lo);
+                            }
+                        }
+                    }
+                    if (l == 0) {
+                        if (ol != 0xff) atomicAdd(&cnts[rowbase + ol], -1);
+                        atomicAdd(&cnts[rowbase + nl], 1);
                     }
                 }
             }
@@ -410,21 +623,20 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
 
         // ---- loss of this assignment (fp64, direct form) and label output
         if (LOSS) {
-            constexpr int RSTEP = kThreads / TP;      // runs covered per pass: 1 (TP = 256) or 2 (TP = 128)
-            const int p = tid % TP;
 #pragma unroll
-            for (int i = 0; i < 8 / RSTEP; ++i) {
+            for (int i = 0; i < NR; ++i) {
                 const int rl = tid / TP + RSTEP * i;
-                if (rl < g.n_runs && p < nvalid) {
-                    const int j = labels_s[p * 8 + rl];
-                    const int crow = rows_before(plan.k_min, g.run0 + rl) + j;
-                    jloc[i] = __dadd_rn(jloc[i], sqdist64(xs + p * XS, Cb + (int64_t)crow * d, d));
+                if (rl < g.n_runs && pr_p < nvalid) {
+                    const int j = labels_s[pr_p * 8 + rl];
+                    const int lrow = rl * k0 + rl * (rl - 1) / 2 + j;
+                    jloc[i] = __dadd_rn(jloc[i], sqdist64(xs + pr_p * XS, cs + lrow * d, d));
                     if (FINAL && a.labels)
-                        a.labels[(int64_t)b * a.lab_bs + (int64_t)(g.run0 + rl) * a.N + p0 + p] = j;
+                        a.labels[(int64_t)b * a.lab_bs + (int64_t)(g.run0 + rl) * a.N + p0 + pr_p] = j;
                 }
             }
         }
         __syncthreads();
+        if (tid == 0) { *qcount_b = 0; *qcount_c = 0; }
     }
 
     if (!FINAL) {
@@ -435,25 +647,20 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         for (int e = tid; e < real_rows; e += kThreads) pcnt[e] = cnts[e];
     }
     if (LOSS) {
-        constexpr int RSTEP = kThreads / TP;
         const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-        for (int i = 0; i < 8 / RSTEP; ++i) {
+        for (int i = 0; i < NR; ++i) {
             double v = jloc[i];
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v = __dadd_rn(v, __shfl_xor(v, off, 64));
-            if (lane == 0) jpart[i * 4 + wave] = v;
+            if (lane == 0) jpart[i * kWaves + wave] = v;
         }
         __syncthreads();
         if (tid < g.n_runs) {
-            const int rl = tid;
-            double v;
-            if (RSTEP == 1) {
-                v = __dadd_rn(__dadd_rn(jpart[rl * 4 + 0], jpart[rl * 4 + 1]), __dadd_rn(jpart[rl * 4 + 2], jpart[rl * 4 + 3]));
-            } else {
-                const int i = rl >> 1, hh = rl & 1;
-                v = __dadd_rn(jpart[i * 4 + 2 * hh], jpart[i * 4 + 2 * hh + 1]);
-            }
+            // run rl was covered by pass rl / RSTEP of the waves whose threads have tid / TP == rl % RSTEP
+            const int rl = tid, i = rl / RSTEP, w0 = (rl % RSTEP) * (kWaves / RSTEP);
+            double v = 0.0;
+            for (int w = 0; w < kWaves / RSTEP; ++w) v = __dadd_rn(v, jpart[i * kWaves + w0 + w]);
             reinterpret_cast<double *>(wsb + a.off_pj)[(int64_t)chunk * plan.n_runs + g.run0 + rl] = v;
         }
     }
@@ -529,9 +736,9 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
         else {
             mean = (float)(t.sum / (double)N);
             if (t.max_msb >= t.min_lsb) {
-                // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk adds
-                // at most 2^17 of them into 63 bits. Bits below the grid (wide columns) go to the low accumulator,
-                // which keeps kLowBits more; anything finer cannot be summed exactly.
+                // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk moves
+                // at most 2^17 rows in and out of a cluster within 63 bits. Bits below the grid (wide columns) go to
+                // the low accumulator, which keeps kLowBits more; anything finer cannot be summed exactly.
                 int grid = t.max_msb - (kGridBits - 1);
                 if (grid < t.min_lsb) grid = t.min_lsb;
                 shift = -grid;
@@ -551,16 +758,42 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     if (l == 0) { colwide[32] = (flags >> 16) & 1; status[b] = flags & 0xffff; }
 }
 
-// ---- operand fill: padding rows are zero vectors with a huge norm ----------------------------
-__global__ void fill_operands_kernel(char *ws, int64_t ws_bs, int64_t off_opA, int64_t off_cn, int64_t n_opA, int64_t n_cn,
-                                     int64_t off_losum, int64_t n_losum)
+// ---- start of a sweep: padding operand rows are zero vectors with a huge norm; running totals are zero;
+//      no point has a label yet
+struct InitArgs {
+    char *ws;
+    int64_t ws_bs;
+    int64_t off_opA, off_losum, off_tot, off_totcnt, off_prev;
+    int64_t n_tiles, n_losum, n_tot, n_totcnt, n_prev16;   // element counts (prev in 16-byte units)
+    int32_t dp;
+};
+__global__ void sweep_init_kernel(InitArgs a)
 {
-    long long *losum = reinterpret_cast<long long *>(ws + (int64_t)blockIdx.y * ws_bs + off_losum);
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_losum; e += (int64_t)gridDim.x * blockDim.x) losum[e] = 0;
-    float *opA = reinterpret_cast<float *>(ws + (int64_t)blockIdx.y * ws_bs + off_opA);
-    float *cn = reinterpret_cast<float *>(ws + (int64_t)blockIdx.y * ws_bs + off_cn);
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_opA; e += (int64_t)gridDim.x * blockDim.x) opA[e] = 0.0f;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_cn; e += (int64_t)gridDim.x * blockDim.x) cn[e] = kPadNorm;
+    char *wsb = a.ws + (int64_t)blockIdx.y * a.ws_bs;
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
+    uint4 *opA = reinterpret_cast<uint4 *>(wsb + a.off_opA);
+    long long *losum = reinterpret_cast<long long *>(wsb + a.off_losum);
+    long long *tot = reinterpret_cast<long long *>(wsb + a.off_tot);
+    long long *totcnt = reinterpret_cast<long long *>(wsb + a.off_totcnt);
+    uint4 *prev = reinterpret_cast<uint4 *>(wsb + a.off_prev);
+    {
+        // a row without a centroid: zero pieces and, in the bias slot, the pieces of a huge squared norm
+        // (lower half-wave) next to the ones that meet the pieces of |x'|^2 (upper half-wave)
+        const int ns = tile_slots_of(a.dp);
+        unsigned ph, pm, pl;
+        split3(kPadNorm, ph, pm, pl);
+        for (int64_t e = t0; e < a.n_tiles * ns * 64; e += step) {
+            const int sl = (int)((e / 64) % ns), ln = (int)(e % 64);
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (sl == ns - 1) v = ln < 32 ? make_uint4(ph | (pm << 16), pl, 0u, 0u) : make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u);
+            opA[e] = v;
+        }
+    }
+    for (int64_t e = t0; e < a.n_losum; e += step) losum[e] = 0;
+    for (int64_t e = t0; e < a.n_tot; e += step) tot[e] = 0;
+    for (int64_t e = t0; e < a.n_totcnt; e += step) totcnt[e] = 0;
+    const uint4 none = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+    for (int64_t e = t0; e < a.n_prev16; e += step) prev[e] = none;
 }
 
 // 128-bit two's complement sum (hi, lo) -> fp64 with one round-to-nearest-even, scaled by 2^-shift
@@ -620,11 +853,11 @@ struct CentroidArgs {
     const int32_t *status;
     char *ws;
     int64_t ws_bs;
-    int64_t off_colinfo, off_opA, off_cn, off_cnmax, off_psum, off_pcnt, off_losum;
+    int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_losum, off_tot, off_totcnt;
 };
 
-// One workgroup per run: new centroids (from the seeding rows, or from the per-chunk partial sums),
-// then the centred, -2-scaled MFMA operand rows and their squared norms.
+// One workgroup per run: new centroids (from the seeding rows, or from the running totals after adding
+// this round's per-chunk deltas), then the centred, -2-scaled MFMA operand rows and their squared norms.
 template <int DP, bool INIT>
 __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan plan, CentroidArgs a)
 {
@@ -643,8 +876,9 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
     const int *colshift = reinterpret_cast<const int *>(wsb + a.off_colinfo + 128);
     const int *colwide = reinterpret_cast<const int *>(wsb + a.off_colinfo + 256);
     float *Cb = a.C + (int64_t)b * a.c_bs;
-    float *opA = reinterpret_cast<float *>(wsb + a.off_opA) + (int64_t)g.tile0 * 32 * DP;
-    float *cn = reinterpret_cast<float *>(wsb + a.off_cn) + (int64_t)g.tile0 * 32;
+    // operand block of the group: per tile, tile_slots_of(DP) slots of 64 lanes x 8 bf16
+    unsigned short *opA = reinterpret_cast<unsigned short *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
+    constexpr int NK = ksteps_of(DP), NS = tile_slots_of(DP);
 
     for (int e = tid; e < k * DP; e += kThreads) {
         const int j = e / DP, l = e % DP;
@@ -658,9 +892,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
             } else {
                 const long long *psum = reinterpret_cast<const long long *>(wsb + a.off_psum);
                 const int *pcnt = reinterpret_cast<const int *>(wsb + a.off_pcnt);
-                long long hi = 0;
-                unsigned long long lo = 0;
-                long long cnt = 0;
+                long long *tot = reinterpret_cast<long long *>(wsb + a.off_tot) + ((int64_t)(row0 + j) * d + l) * 2;
+                long long *totcnt = reinterpret_cast<long long *>(wsb + a.off_totcnt) + (int64_t)(row0 + j) * d + l;
+                long long hi = tot[0];
+                unsigned long long lo = (unsigned long long)tot[1];
+                long long cnt = *totcnt;
                 for (int c0 = 0; c0 < plan.n_chunks; ++c0) {
                     const long long v = psum[((int64_t)c0 * plan.total_rows + row0 + j) * d + l];
                     const unsigned long long nlo = lo + (unsigned long long)v;
@@ -668,12 +904,13 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
                     lo = nlo;
                     cnt += pcnt[(int64_t)c0 * plan.total_rows + row0 + j];
                 }
+                tot[0] = hi;
+                tot[1] = (long long)lo;
+                *totcnt = cnt;
                 int shift = colshift[l];
                 if (colwide[l]) {
                     // total = main * 2^kLowBits + low, on the scale 2^-(shift + kLowBits)
-                    long long *losum = reinterpret_cast<long long *>(wsb + a.off_losum) + (int64_t)(row0 + j) * d + l;
-                    const long long low = *losum;
-                    *losum = 0;
+                    const long long low = reinterpret_cast<const long long *>(wsb + a.off_losum)[(int64_t)(row0 + j) * d + l];
                     hi = (long long)(((unsigned long long)hi << kLowBits) | (lo >> (64 - kLowBits)));
                     lo = lo << kLowBits;
                     const unsigned long long nlo = lo + (unsigned long long)low;
@@ -695,8 +932,13 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         const int qd = j >> 2, i = j & 3;
         const int t = qd / g.S, slot = rl * g.S + qd % g.S;
         const int m = 8 * (slot & 3) + 4 * (slot >> 2) + i;
-        const int h = l / (DP / 2), s = l % (DP / 2);
-        opA[((((t * 2 + h) * (DP / 8) + (s >> 2)) * 32 + m) << 2) + (s & 3)] = -2.0f * cp;
+        const int h = l / (DP / 2), sf = l % (DP / 2);
+        unsigned ph, pm, pl;
+        split3(-2.0f * cp, ph, pm, pl);
+        const int ks = sf >> 3, el = sf & 7, ln = h * 32 + m;
+        opA[((int64_t)(t * NS + 0 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)ph;
+        opA[((int64_t)(t * NS + 1 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)pm;
+        opA[((int64_t)(t * NS + 2 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)pl;
     }
     __syncthreads();
     float mx = 0.0f;
@@ -705,7 +947,12 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         for (int l = 0; l < DP; ++l) nrm = fmaf(cs[j * DP + l], cs[j * DP + l], nrm);
         const int qd = j >> 2, i = j & 3;
         const int t = qd / g.S, slot = rl * g.S + qd % g.S;
-        cn[t * 32 + 8 * (slot & 3) + 4 * (slot >> 2) + i] = nrm;
+        // bias slot, lower half-wave lane of this row: pieces of the squared norm
+        unsigned ph, pm, pl;
+        split3(nrm, ph, pm, pl);
+        const int m = 8 * (slot & 3) + 4 * (slot >> 2) + i;
+        unsigned short *bias = opA + ((int64_t)(t * NS + 3 * NK) * 64 + m) * 8;
+        bias[0] = (unsigned short)ph; bias[1] = (unsigned short)pm; bias[2] = (unsigned short)pl;
         mx = fmaxf(mx, nrm);
     }
     for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
@@ -752,17 +999,21 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
                        a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
     hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(32), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
                        L.per_batch, L.colstat_part, L.colinfo, a.status);
-    hipLaunchKernelGGL(fill_operands_kernel, dim3(64, batch), dim3(256), 0, s, a.ws, L.per_batch, L.opA, L.cn,
-                       (int64_t)plan.total_tiles * 32 * DP, (int64_t)plan.total_tiles * 32, L.losum,
-                       (int64_t)plan.total_rows * a.d);
+    InitArgs ia;
+    ia.ws = a.ws; ia.ws_bs = L.per_batch;
+    ia.off_opA = L.opA; ia.off_losum = L.losum; ia.off_tot = L.tot; ia.off_totcnt = L.totcnt; ia.off_prev = L.prev;
+    ia.n_tiles = plan.total_tiles; ia.dp = DP;
+    ia.n_losum = (int64_t)plan.total_rows * a.d; ia.n_tot = ia.n_losum * 2; ia.n_totcnt = ia.n_losum;
+    ia.n_prev16 = ((int64_t)plan.n_runs * a.N + 15) / 16;
+    hipLaunchKernelGGL(sweep_init_kernel, dim3(512, batch), dim3(256), 0, s, ia);
 
     CentroidArgs ca;
     ca.X = a.X; ca.N = a.N; ca.d = a.d; ca.ldx = a.ldx; ca.x_bs = a.x_batch_stride;
     ca.init_idx = a.init_idx; ca.init_bs = a.init_batch_stride;
     ca.C = a.centroids; ca.c_bs = (int64_t)plan.total_rows * a.d;
     ca.status = a.status; ca.ws = a.ws; ca.ws_bs = L.per_batch;
-    ca.off_colinfo = L.colinfo; ca.off_opA = L.opA; ca.off_cn = L.cn; ca.off_cnmax = L.cnmax;
-    ca.off_psum = L.psum; ca.off_pcnt = L.pcnt; ca.off_losum = L.losum;
+    ca.off_colinfo = L.colinfo; ca.off_opA = L.opA; ca.off_cnmax = L.cnmax;
+    ca.off_psum = L.psum; ca.off_pcnt = L.pcnt; ca.off_losum = L.losum; ca.off_tot = L.tot; ca.off_totcnt = L.totcnt;
     hipLaunchKernelGGL((lloyd_centroids_kernel<DP, true>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
 
     StepArgs sa;
@@ -770,28 +1021,34 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     sa.C = a.centroids; sa.c_bs = ca.c_bs;
     sa.labels = a.labels; sa.lab_bs = (int64_t)plan.n_runs * a.N;
     sa.status = a.status; sa.ws = a.ws; sa.ws_bs = L.per_batch;
-    sa.off_colinfo = L.colinfo; sa.off_opA = L.opA; sa.off_cn = L.cn; sa.off_cnmax = L.cnmax;
-    sa.off_psum = L.psum; sa.off_pcnt = L.pcnt; sa.off_pj = L.pj; sa.off_losum = L.losum;
+    sa.off_colinfo = L.colinfo; sa.off_opA = L.opA; sa.off_cnmax = L.cnmax;
+    sa.off_psum = L.psum; sa.off_pcnt = L.pcnt; sa.off_pj = L.pj; sa.off_losum = L.losum; sa.off_prev = L.prev;
 
     size_t lds = 0;
     for (int gi = 0; gi < plan.n_groups; ++gi) {
         const GroupDesc &g = plan.g[gi];
         const int rr = rows_before(plan.k_min, g.run0 + g.n_runs) - rows_before(plan.k_min, g.run0);
-        const size_t need = (size_t)carve_lds(DP, g.n_tiles, rr).total;
+        const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr, g.cs_lds != 0).total;
         if (need > lds) lds = need;
     }
     const dim3 grid(plan.n_groups * plan.n_chunks, batch);
     const bool trace = a.trace != nullptr;
+    const bool prof = profile_enabled();
     for (int t = 0; t < a.iters; ++t) {
+        sa.first_round = t == 0 ? 1 : 0;
+        if (prof) { hipError_t e = profile_mark(s, true); if (e != hipSuccess) return e; }
         if (trace) {
             hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(kThreads), lds, s, plan, sa);
+            if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
             hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws,
                                L.per_batch, L.pj, a.trace, (int64_t)plan.n_runs * (a.iters + 1), (int64_t)(a.iters + 1), (int64_t)t);
         } else {
             hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false>), grid, dim3(kThreads), lds, s, plan, sa);
+            if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
         }
         hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
     }
+    sa.first_round = 0;
     hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false>), grid, dim3(kThreads), lds, s, plan, sa);
     hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws, L.per_batch,
                        L.pj, a.inertia, (int64_t)plan.n_runs, (int64_t)1, (int64_t)0);
@@ -811,14 +1068,13 @@ LloydGeometry lloyd_geometry(int dp)
     LloydGeometry g;
     g.threads = kThreads;
     g.tile_points = tile_points_of(dp);
-    g.lds_budget = 80 * 1024;
+    g.lds_budget = 156 * 1024;
     return g;
 }
 
-int64_t lloyd_group_lds_bytes(int dp, int tile_points, int n_tiles, int real_rows)
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, bool with_cs)
 {
-    (void)tile_points;
-    return carve_lds(dp, n_tiles, real_rows).total;
+    return carve_lds(dp, d, n_tiles, real_rows, with_cs).total;
 }
 
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan)
@@ -832,8 +1088,12 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
     int tiles = 0;
     int run = 0;
     while (run < plan->n_runs) {
-        bool placed = false;
-        for (int R = 8; R >= 1 && !placed; R >>= 1) {
+        // candidates: R runs side by side (8 / R slots each), with or without the LDS copy of the centroids;
+        // take the one with the least padding per real row, preferring the copy and then the larger R
+        int best_R = 0, best_tiles = 0, best_nr = 0;
+        bool best_cs = false;
+        double best_score = 1e30;
+        for (int R = 8; R >= 1; R >>= 1) {
             const int S = 8 / R;
             const int nr = plan->n_runs - run < R ? plan->n_runs - run : R;
             const int kmax_g = k_min + run + nr - 1;
@@ -841,22 +1101,29 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
             const int n_tiles = (quads + S - 1) / S;
             const int real_rows = rows_before(k_min, run + nr) - rows_before(k_min, run);
             if (n_tiles > 32) continue;
-            if (lloyd_group_lds_bytes(dp, geo.tile_points, n_tiles, real_rows) > geo.lds_budget) continue;
-            if (plan->n_groups >= kMaxGroups) return RLS_ERR_INVALID_ARG;
-            GroupDesc &g = plan->g[plan->n_groups++];
-            g.run0 = (int16_t)run; g.n_runs = (int16_t)nr; g.S = (int16_t)S; g.n_tiles = (int16_t)n_tiles; g.tile0 = tiles;
-            tiles += n_tiles;
-            run += nr;
-            placed = true;
+            for (int with_cs = 1; with_cs >= 0; --with_cs) {
+                if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows, with_cs != 0) > geo.lds_budget) continue;
+                // cost per real row: padded rows, a fixed per-group overhead, and a small penalty for the missing copy
+                const double score = (n_tiles * 32.0 + 24.0) / real_rows + (with_cs ? 0.0 : 0.02);
+                if (score < best_score - 1e-12) {
+                    best_score = score; best_R = R; best_tiles = n_tiles; best_nr = nr; best_cs = with_cs != 0;
+                }
+                break;
+            }
         }
-        if (!placed) return RLS_ERR_INVALID_ARG;
+        if (best_R == 0 || plan->n_groups >= kMaxGroups) return RLS_ERR_INVALID_ARG;
+        GroupDesc &g = plan->g[plan->n_groups++];
+        g.run0 = (int16_t)run; g.n_runs = (int16_t)best_nr; g.S = (int16_t)(8 / best_R); g.n_tiles = (int16_t)best_tiles;
+        g.cs_lds = best_cs ? 1 : 0; g.pad = 0; g.tile0 = tiles;
+        tiles += best_tiles;
+        run += best_nr;
     }
     plan->total_tiles = tiles;
     plan->total_rows = rows_before(k_min, plan->n_runs);
     // chunks: enough workgroups to fill the chip several times over; a chunk never exceeds 2^17 points
     const int tp = geo.tile_points;
     const int64_t tiles_total = (N + tp - 1) / tp;
-    int64_t want = (4096 + plan->n_groups - 1) / plan->n_groups;
+    int64_t want = (1024 + plan->n_groups - 1) / plan->n_groups;
     if (want > tiles_total) want = tiles_total;
     if (want < 1) want = 1;
     int64_t chunk_len = ((tiles_total + want - 1) / want) * tp;
@@ -880,13 +1147,15 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->chain = take((int64_t)k_max * 8);
     L->mind = take(N * 8);
     L->bsum = take((int64_t)L->seed_blocks * 8);
-    L->opA = take((int64_t)plan.total_tiles * 32 * plan.dp * 4);
-    L->cn = take((int64_t)plan.total_tiles * 32 * 4);
+    L->opA = take((int64_t)plan.total_tiles * tile_bytes_of(plan.dp));
     L->cnmax = take((int64_t)plan.n_runs * 4);
     L->psum = take((int64_t)plan.n_chunks * plan.total_rows * d * 8);
     L->pcnt = take((int64_t)plan.n_chunks * plan.total_rows * 4);
     L->pj = take((int64_t)plan.n_chunks * plan.n_runs * 8);
     L->losum = take((int64_t)plan.total_rows * d * 8);
+    L->tot = take((int64_t)plan.total_rows * d * 16);
+    L->totcnt = take((int64_t)plan.total_rows * d * 8);
+    L->prev = take(align_up((int64_t)plan.n_runs * N, 16));
     L->per_batch = off;
     L->total = off * batch;
 }

@@ -11,6 +11,25 @@ namespace rls {
 static thread_local hipError_t g_last_hip = hipSuccess;
 void set_hip_error(hipError_t e) { g_last_hip = e; }
 
+// ---- benchmark timing: event pairs around the Lloyd step kernel --------------------------------
+static bool g_profile_on = false;
+static std::vector<hipEvent_t> g_events;     // pool, reused
+static size_t g_events_used = 0;             // events recorded since the last read (even: begin, odd: end)
+
+bool profile_enabled() { return g_profile_on; }
+
+hipError_t profile_mark(hipStream_t s, bool begin)
+{
+    if (begin != (g_events_used % 2 == 0)) return hipSuccess;   // keep pairs aligned
+    if (g_events_used == g_events.size()) {
+        hipEvent_t ev;
+        hipError_t e = hipEventCreate(&ev);
+        if (e != hipSuccess) return e;
+        g_events.push_back(ev);
+    }
+    return hipEventRecord(g_events[g_events_used++], s);
+}
+
 static int32_t check_matrix(const float *X, int64_t N, int32_t d, int64_t ldx)
 {
     if (!X) return RLS_ERR_NULL;
@@ -59,6 +78,29 @@ const char *rls_error_string(int32_t code)
 }
 
 int32_t rls_last_hip_error(void) { return (int32_t)g_last_hip; }
+
+int32_t rls_profile_enable(int32_t on)
+{
+    g_profile_on = on != 0;
+    return RLS_OK;
+}
+
+int32_t rls_profile_read(int32_t *n_launches, double *total_ms)
+{
+    if (!n_launches || !total_ms) return RLS_ERR_NULL;
+    double sum = 0.0;
+    const size_t pairs = g_events_used / 2;
+    for (size_t i = 0; i < pairs; ++i) {
+        RLS_HIP_TRY(hipEventSynchronize(g_events[2 * i + 1]));
+        float ms = 0.0f;
+        RLS_HIP_TRY(hipEventElapsedTime(&ms, g_events[2 * i], g_events[2 * i + 1]));
+        sum += (double)ms;
+    }
+    g_events_used = 0;
+    *n_launches = (int32_t)pairs;
+    *total_ms = sum;
+    return RLS_OK;
+}
 
 int32_t rls_gbt_score_batched(const rls_forest *forests, int32_t batch, const float *X_dev, int64_t N, int32_t d,
                               int64_t ldx, int64_t x_batch_stride, float *score_dev, void *stream)

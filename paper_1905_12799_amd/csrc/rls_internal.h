@@ -34,6 +34,8 @@ struct GroupDesc {
     int16_t n_runs;    // real runs in this group (<= 8 / S)
     int16_t S;         // slots per run: 1, 2, 4 or 8
     int16_t n_tiles;   // 32-row tiles
+    int16_t cs_lds;    // 1: the group's centroids (as given) are also copied to LDS
+    int16_t pad;
     int32_t tile0;     // tiles of all earlier groups (offset of this group's operand block)
 };
 
@@ -64,7 +66,7 @@ struct LloydGeometry {
 LloydGeometry lloyd_geometry(int dp);
 int padded_d(int d);
 // LDS bytes of a group: fixed part + operand tiles + exact-sum accumulators
-int64_t lloyd_group_lds_bytes(int dp, int tile_points, int n_tiles, int real_rows);
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, bool with_cs);
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan);
 
 // Workspace carving for one sweep (all offsets in bytes from the workspace base, per batch element
@@ -75,13 +77,15 @@ struct SweepLayout {
     int64_t chain;          // int64 [k_max] seeding chain
     int64_t mind;           // fp64 [N] squared distance to the nearest chosen centre
     int64_t bsum;           // fp64 [seed blocks] block sums of mind
-    int64_t opA;            // fp32 [total_tiles * 32 * dp] centred, -2-scaled centroids in MFMA operand order
-    int64_t cn;             // fp32 [total_tiles * 32] squared norms of the centred centroids (padding: huge)
+    int64_t opA;            // per 32-row tile: bf16 pieces of the centred, -2-scaled centroids and the bias slot, in MFMA operand order
     int64_t cnmax;          // fp32 [n_runs] per-run maximum of cn
-    int64_t psum;           // int64 [n_chunks][total_rows][d] partial fixed-point sums
-    int64_t pcnt;           // int32 [n_chunks][total_rows] partial counts
+    int64_t psum;           // int64 [n_chunks][total_rows][d] per-chunk changes of the fixed-point sums
+    int64_t pcnt;           // int32 [n_chunks][total_rows] per-chunk changes of the member counts
     int64_t pj;             // fp64 [n_chunks][n_runs] partial losses
-    int64_t losum;          // int64 [total_rows][d] low-order fixed-point sums of wide columns
+    int64_t losum;          // int64 [total_rows][d] low-order fixed-point sums of wide columns (running)
+    int64_t tot;            // int64 [total_rows][d][2] running 128-bit fixed-point sums (hi, lo)
+    int64_t totcnt;         // int64 [total_rows][d] running member counts (one copy per feature)
+    int64_t prev;           // uint8 [n_runs][N] label of every point in the last round (0xff: none yet)
     int64_t per_batch;      // bytes per batch element (multiple of 256)
     int64_t total;          // per_batch * batch
     int32_t seed_blocks;
@@ -134,6 +138,10 @@ struct SweepArgs {
     int32_t *status;              // [batch]
     char *ws;                     // workspace base
 };
+// benchmark timing of the Lloyd step kernel (see rls_profile_enable)
+bool profile_enabled();
+hipError_t profile_mark(hipStream_t s, bool begin);
+
 hipError_t launch_sweep(const SweepPlan &plan, const SweepLayout &L, const SweepArgs &a, hipStream_t s);
 
 }  // namespace rls
