@@ -174,7 +174,7 @@ def main() -> int:
         import oracle
         p0 = probs[0]
         ks = [k for k in (8, 32, 64, 128) if w.k_min <= k <= w.k_max] or [w.k_max]
-        iters_s = 3
+        iters_s = 20
         chain = oracle.kmeanspp_chain(p0.X, max(ks), w.seed)
         t = time.perf_counter()
         for k in ks:
