@@ -8,9 +8,9 @@
 //            leading cross products are accumulated in fp32 (fp32-class accuracy; the bf16 pipeline runs
 //            beside the vector ALU, the fp32 one does not); per point and run, the best and second-best
 //            packed (value, index) keys
-//   phase B  points whose two best keys are closer than the error bound of phase A are decided
-//            again in fp64 with the direct form sum_l (x_l - c_l)^2 - the arithmetic that defines
-//            the assignment - so labels do not depend on fp32 cancellation
+//            pairs whose two best keys are closer than the error bound of these distances are decided
+//            again, by the whole wave, in fp64 with the direct form sum_l (x_l - c_l)^2 - the arithmetic
+//            that defines the assignment - so labels do not depend on fp32 cancellation
 //   phase C  exact centroid sums, kept as running totals: only points whose label differs from the one
 //            of the previous round move their fixed-point row from the old cluster's int64 accumulators
 //            to the new one's (integer adds commute and cancel exactly, so the totals equal a fresh sum
@@ -42,7 +42,7 @@ __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(d
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
 struct Carve {
-    int xs, opA, cs, sums, cnts, labels, old, queue_b, queue_c, misc, total;
+    int xs, opA, cs, sums, cnts, labels, old, queue_c, misc, total;
 };
 __host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows, bool with_cs)
 {
@@ -51,12 +51,11 @@ __host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_
     int off = 0;
     c.xs = off;      off += tp * (dp + 4) * 4;                 // raw tile rows, padded stride
     c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (bf16 pieces + bias)
-    c.cs = off;      off += with_cs ? (real_rows * d * 4 + 15) / 16 * 16 : 0;   // centroids as given (for fp64 distances)
+    c.cs = off;      off += with_cs ? real_rows * (d + 4) * 4 / 16 * 16 + 16 : 0;   // centroids as given, row stride d + 4
     c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point delta sums
     c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
     c.labels = off;  off += tp * 8;                            // labels of the tile, [point][run]
     c.old = off;     off += tp * 8;                            // previous labels of queued points
-    c.queue_b = off; off += tp * 8 * 2;                        // (point, run) pairs to decide again in fp64
     c.queue_c = off; off += tp * 8 * 2;                        // (point, run) pairs whose label changed
     c.misc = off;    off += 1024;
     c.total = off;
@@ -132,6 +131,45 @@ __device__ inline double sqdist64(const float *x, const float *c, int d)
     return acc;
 }
 
+// same sum, rows read 16 bytes at a time (d a multiple of 4, both rows 16-byte aligned)
+__device__ inline double sqdist64_v4(const float *x, const float *c, int d)
+{
+    double acc = 0.0;
+    for (int l = 0; l < d; l += 4) {
+        const float4 xv = *reinterpret_cast<const float4 *>(x + l), cv = *reinterpret_cast<const float4 *>(c + l);
+        double diff = __dsub_rn((double)xv.x, (double)cv.x);
+        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+        diff = __dsub_rn((double)xv.y, (double)cv.y);
+        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+        diff = __dsub_rn((double)xv.z, (double)cv.z);
+        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+        diff = __dsub_rn((double)xv.w, (double)cv.w);
+        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+    }
+    return acc;
+}
+
+// The assignment as it is defined, by one whole wave: fp64 direct-form distances of one point to the k
+// centroids of a run (one or two per lane), then the lexicographic minimum of (distance, index) over the wave.
+// Every lane returns the winner.
+__device__ inline int exact_argmin_wave(const float *xrow, const float *crun, int cstride, int k, int d, bool vec)
+{
+    const int lane = threadIdx.x & 63;
+    double best = INFINITY;
+    int arg = 0x7fffffff;
+    for (int j = lane; j < k; j += 64) {
+        const double dist = vec ? sqdist64_v4(xrow, crun + j * cstride, d) : sqdist64(xrow, crun + j * cstride, d);
+        if (dist < best) { best = dist; arg = j; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const double ob = __shfl_xor(best, off, 64);
+        const int oa = __shfl_xor(arg, off, 64);
+        if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+    }
+    return arg;
+}
+
 // v = h + m + l exactly, each piece a bf16 (8 significant bits): h and m by truncation, l is what is left
 __device__ inline void split3(float v, unsigned &h, unsigned &m, unsigned &l)
 {
@@ -196,8 +234,11 @@ struct PhaseACtx {
     const float *xs, *mu_s, *cnmax_s;
     const uint4 *opA_s;
     unsigned char *labels_s, *old_s;
-    unsigned short *queue_b, *queue_c;
-    int *qcount_b, *qcount_c;
+    unsigned short *queue_c;
+    int *qcount_c;
+    const float *cs;              // the group's centroids as given (LDS copy or global), row stride cs_stride
+    int cs_stride, k0, d;
+    bool vec;                     // rows may be read 16 bytes at a time
     unsigned char *prev_tile;     // global: previous labels, prev_tile[rl * prev_stride + p]; null when not tracked
     int64_t prev_stride;
     int n_tiles, n_runs_g, nvalid;
@@ -354,29 +395,37 @@ __device__ inline void phase_a(const PhaseACtx &c)
 #pragma unroll
         for (int st = 0; st < ST; ++st) {
             const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
-            const bool writer = (S == 8) ? (hl == 0) : true;
-            if (!writer || rl >= c.n_runs_g) continue;
-            unsigned char lab = 0xff;
-            if (p < c.nvalid) {
+            const bool writer = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs_g;
+            const bool active = writer && p < c.nvalid;
+            int lab = 0xff;
+            bool close = false;
+            if (active) {
                 const int k1 = m1[pb][st], k2 = m2[pb][st];
-                lab = (unsigned char)(k1 & 127);
+                lab = k1 & 127;
                 const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
-                // error bound of the fp32 expansion (rounding of norms, products and the centring) plus the
+                // error bound of the expansion (rounding of norms, products and the centring) plus the
                 // 7 mantissa bits given up to the index in each key
                 const float tol = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 6.2e-5f * fabsf(f2) + 1.0e-30f;
-                if (!(f2 - f1 > tol)) {
-                    // too close to call in fp32: phase B decides (and then looks at the previous label)
-                    const int slot = atomicAdd(c.qcount_b, 1);
-                    c.queue_b[slot] = (unsigned short)(p | (rl << 9));
-                    c.old_s[p * 8 + rl] = oldl[pb][st];
-                } else if (c.prev_tile && lab != oldl[pb][st]) {
-                    const int slot = atomicAdd(c.qcount_c, 1);
-                    c.queue_c[slot] = (unsigned short)(p | (rl << 9));
-                    c.old_s[p * 8 + rl] = oldl[pb][st];
-                    c.prev_tile[rl * c.prev_stride + p] = lab;
-                }
+                close = !(f2 - f1 > tol);
             }
-            c.labels_s[p * 8 + rl] = lab;
+            // too close to call: the wave decides these pairs one after the other with the exact arithmetic
+            unsigned long long todo = __ballot(close);
+            while (todo) {
+                const int src = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                const int sp = wave * 32 * NB + pb * 32 + (src & 31);
+                const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
+                const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * c.cs_stride;
+                const int arg = exact_argmin_wave(xs + sp * XS, crun, c.cs_stride, c.k0 + srl, c.d, c.vec);
+                if (lane == src) lab = arg;
+            }
+            if (active && c.prev_tile && lab != (int)oldl[pb][st]) {
+                const int slot = atomicAdd(c.qcount_c, 1);
+                c.queue_c[slot] = (unsigned short)(p | (rl << 9));
+                c.old_s[p * 8 + rl] = oldl[pb][st];
+                c.prev_tile[rl * c.prev_stride + p] = (unsigned char)lab;
+            }
+            if (writer) c.labels_s[p * 8 + rl] = (unsigned char)lab;
         }
     }
 }
@@ -414,13 +463,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     int *cnts = reinterpret_cast<int *>(smem + cv.cnts);
     unsigned char *labels_s = smem + cv.labels;
     unsigned char *old_s = smem + cv.old;
-    unsigned short *queue_b = reinterpret_cast<unsigned short *>(smem + cv.queue_b);
     unsigned short *queue_c = reinterpret_cast<unsigned short *>(smem + cv.queue_c);
     float *mu_s = reinterpret_cast<float *>(smem + cv.misc);              // [32]
     int *shift_s = reinterpret_cast<int *>(smem + cv.misc + 128);         // [32]
     int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
     float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
-    int *qcount_b = reinterpret_cast<int *>(smem + cv.misc + 432);
     int *qcount_c = reinterpret_cast<int *>(smem + cv.misc + 436);
     double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][kWaves]
 
@@ -443,19 +490,20 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
         if (g.cs_lds) {
             const float *csrc = Cb + (int64_t)grow0 * d;
-            for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[e] = csrc[e];
+            for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[(e / d) * (d + 4) + e % d] = csrc[e];
         }
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
         if (!FINAL) {
             for (int e = tid; e < real_rows * (DP + 1); e += kThreads) sums[e] = 0ull;
             for (int e = tid; e < real_rows; e += kThreads) cnts[e] = 0;
         }
-        if (tid == 0) { *qcount_b = 0; *qcount_c = 0; }
+        if (tid == 0) *qcount_c = 0;
     }
     __syncthreads();
 
     // the group's centroids as given: the LDS copy, or global memory when the copy did not fit
     const float *cs = g.cs_lds ? cs_lds : Cb + (int64_t)grow0 * d;
+    const int cs_stride = g.cs_lds ? d + 4 : d;
     const int l = tid % DP, pg = tid / DP;                           // (point, feature) mapping
     const int l4 = (tid % TPP) * 4, pg4 = tid / TPP;                 // (point, 4 features) mapping
     const int my_shift = shift_s[l];
@@ -501,8 +549,10 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
 
     PhaseACtx ctx;
     ctx.xs = xs; ctx.opA_s = opA_s; ctx.mu_s = mu_s; ctx.cnmax_s = cnmax_s;
-    ctx.labels_s = labels_s; ctx.old_s = old_s; ctx.queue_b = queue_b; ctx.queue_c = queue_c;
-    ctx.qcount_b = qcount_b; ctx.qcount_c = qcount_c;
+    ctx.labels_s = labels_s; ctx.old_s = old_s; ctx.queue_c = queue_c; ctx.qcount_c = qcount_c;
+    ctx.cs = cs; ctx.cs_stride = cs_stride; ctx.k0 = k0; ctx.d = d;
+    // 16-byte reads of centroid rows: LDS copy (padded stride) or global rows, both with d a multiple of 4
+    ctx.vec = (d % 4 == 0) && (g.cs_lds || (reinterpret_cast<uintptr_t>(cs) & 15) == 0);
     ctx.prev_stride = a.N; ctx.n_tiles = g.n_tiles; ctx.n_runs_g = g.n_runs; ctx.eps_a = eps_a;
 
     for (int64_t p0 = chunk_begin; p0 < chunk_end; p0 += TP) {
@@ -513,7 +563,8 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         fetch_tile(p0 + TP);
         __syncthreads();
 
-        // ---- phase A (the lanes that own a (point, run) result also compare it with the previous label)
+        // ---- phase A (the lanes that own a (point, run) result also settle close calls and compare the label
+        //      with the one of the previous round)
         ctx.nvalid = nvalid;
         ctx.prev_tile = track ? prev + (int64_t)g.run0 * a.N + p0 : nullptr;
         switch (g.S) {
@@ -521,39 +572,6 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         case 2: phase_a<DP, 2>(ctx); break;
         case 4: phase_a<DP, 4>(ctx); break;
         default: phase_a<DP, 8>(ctx); break;
-        }
-        __syncthreads();
-
-        // ---- phase B: exact fp64 decision for the queued (point, run) pairs, one pair per wave at a time
-        {
-            const int nq = *qcount_b;
-            const int lane = tid & 63, wave = tid >> 6;
-            for (int e = wave; e < nq; e += kWaves) {
-                const int ent = queue_b[e];
-                const int p = ent & 511, rl = ent >> 9;
-                const int k = k0 + rl;
-                const float *crun = cs + (rl * k0 + rl * (rl - 1) / 2) * d;
-                double best = INFINITY;
-                int arg = 0x7fffffff;
-                for (int j = lane; j < k; j += 64) {
-                    const double dist = sqdist64(xs + p * XS, crun + j * d, d);
-                    if (dist < best) { best = dist; arg = j; }
-                }
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const double ob = __shfl_xor(best, off, 64);
-                    const int oa = __shfl_xor(arg, off, 64);
-                    if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
-                }
-                if (lane == 0) {
-                    labels_s[p * 8 + rl] = (unsigned char)arg;
-                    if (track && arg != (int)old_s[p * 8 + rl]) {
-                        const int slot = atomicAdd(qcount_c, 1);
-                        queue_c[slot] = (unsigned short)ent;
-                        prev[(int64_t)(g.run0 + rl) * a.N + p0 + p] = (unsigned char)arg;
-                    }
-                }
-            }
         }
         __syncthreads();
 
@@ -629,14 +647,14 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
                 if (rl < g.n_runs && pr_p < nvalid) {
                     const int j = labels_s[pr_p * 8 + rl];
                     const int lrow = rl * k0 + rl * (rl - 1) / 2 + j;
-                    jloc[i] = __dadd_rn(jloc[i], sqdist64(xs + pr_p * XS, cs + lrow * d, d));
+                    jloc[i] = __dadd_rn(jloc[i], sqdist64(xs + pr_p * XS, cs + lrow * cs_stride, d));
                     if (FINAL && a.labels)
                         a.labels[(int64_t)b * a.lab_bs + (int64_t)(g.run0 + rl) * a.N + p0 + pr_p] = j;
                 }
             }
         }
         __syncthreads();
-        if (tid == 0) { *qcount_b = 0; *qcount_c = 0; }
+        if (tid == 0) *qcount_c = 0;
     }
 
     if (!FINAL) {
