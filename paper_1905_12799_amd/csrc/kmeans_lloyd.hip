@@ -1,22 +1,24 @@
 // Lloyd's k-means for every k of a range at once: the "k-means(s_Theta, k)" call inside the loop of
 // Algorithm 1 (Sec. 4.2 of the paper), all k side by side, iterations in lock step.
 //
-// Per iteration one launch of lloyd_step_kernel does, for every (group of runs, chunk of points):
-//   phase 0  load a tile of points (raw fp32) into LDS; the next tile's rows travel in registers meanwhile
-//   phase A  distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means, on the
+// Per iteration one launch of lloyd_step_kernel covers every (group of runs, chunk of points).  A workgroup
+// stages its group's operand rows, a copy of its centroids and integer accumulators in LDS once; then each of
+// its eight waves works through its own points without any barrier:
+//   load     each lane loads its half of the features of its points straight into registers, one step ahead
+//   assign   distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means, on the
 //            bf16 matrix pipeline: every fp32 operand is split exactly into three bf16 pieces and the six
 //            leading cross products are accumulated in fp32 (fp32-class accuracy; the bf16 pipeline runs
-//            beside the vector ALU, the fp32 one does not); per point and run, the best and second-best
-//            packed (value, index) keys
-//            pairs whose two best keys are closer than the error bound of these distances are decided
-//            again, by the whole wave, in fp64 with the direct form sum_l (x_l - c_l)^2 - the arithmetic
-//            that defines the assignment - so labels do not depend on fp32 cancellation
-//   phase C  exact centroid sums, kept as running totals: only points whose label differs from the one
+//            beside the vector ALU, the fp32 one does not); per point and run the three smallest packed
+//            (value, index) keys are kept.  When the two best are closer than the error bound of these
+//            distances the pair is decided again in fp64 with the direct form sum_l (x_l - c_l)^2 - the
+//            arithmetic that defines the assignment - by the lane itself if the third key is clear of the
+//            bound, else by a scan of the whole run; labels never depend on fp32 or bf16 rounding
+//   update   exact centroid sums, kept as running totals: only points whose label differs from the one
 //            of the previous round move their fixed-point row from the old cluster's int64 accumulators
-//            to the new one's (integer adds commute and cancel exactly, so the totals equal a fresh sum
-//            in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel adds them to
-//            the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
-// The final pass replaces phase C by the fp64 loss of every point and the label output.
+//            to the new one's (integer LDS atomics; integer adds commute and cancel exactly, so the totals
+//            equal a fresh sum in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel
+//            adds them to the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
+// The final pass replaces the update by the fp64 loss of every point and the label output.
 #include "rls_internal.h"
 
 namespace rls {
@@ -42,21 +44,16 @@ __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(d
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
 struct Carve {
-    int xs, opA, cs, sums, cnts, labels, old, queue_c, misc, total;
+    int opA, cs, sums, cnts, misc, total;
 };
-__host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows, bool with_cs)
+__host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows)
 {
-    const int tp = tile_points_of(dp);
     Carve c;
     int off = 0;
-    c.xs = off;      off += tp * (dp + 4) * 4;                 // raw tile rows, padded stride
     c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (bf16 pieces + bias)
-    c.cs = off;      off += with_cs ? real_rows * (d + 4) * 4 / 16 * 16 + 16 : 0;   // centroids as given, row stride d + 4
-    c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point delta sums
+    c.cs = off;      off += real_rows * (d + 4) * 4 / 16 * 16 + 16;        // centroids as given, row stride d + 4
+    c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point sum deltas
     c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
-    c.labels = off;  off += tp * 8;                            // labels of the tile, [point][run]
-    c.old = off;     off += tp * 8;                            // previous labels of queued points
-    c.queue_c = off; off += tp * 8 * 2;                        // (point, run) pairs whose label changed
     c.misc = off;    off += 1024;
     c.total = off;
     return c;
@@ -76,7 +73,6 @@ struct StepArgs {
     char *ws;                // workspace base
     int64_t ws_bs;           // bytes per batch element
     int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev;
-    int32_t first_round;     // 1: no point has a label yet (every assignment is a change)
 };
 
 // x * 2^shift truncated toward zero; exact whenever x is a multiple of 2^-shift
@@ -149,6 +145,37 @@ __device__ inline double sqdist64_v4(const float *x, const float *c, int d)
     return acc;
 }
 
+// half of a centroid row (the features of one half-wave) from LDS into registers
+template <int H>
+__device__ inline void load_half_row(float (&dst)[H], const float *src, int nf, bool vec)
+{
+    if (vec) {
+#pragma unroll
+        for (int l = 0; l < H; l += 4) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (l < nf) v = *reinterpret_cast<const float4 *>(src + l);
+            dst[l] = v.x; dst[l + 1] = v.y; dst[l + 2] = v.z; dst[l + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int l = 0; l < H; ++l) dst[l] = l < nf ? src[l] : 0.0f;
+    }
+}
+
+// continues the fp64 direct-form sum `acc` over nf more features held in registers
+template <int H>
+__device__ inline double sqdist64_cont(double acc, const float (&x)[H], const float (&c)[H], int nf)
+{
+#pragma unroll
+    for (int l = 0; l < H; ++l) {
+        if (l < nf) {
+            const double diff = __dsub_rn((double)x[l], (double)c[l]);
+            acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+        }
+    }
+    return acc;
+}
+
 // The assignment as it is defined, by one whole wave: fp64 direct-form distances of one point to the k
 // centroids of a run (one or two per lane), then the lexicographic minimum of (distance, index) over the wave.
 // Every lane returns the winner.
@@ -206,93 +233,146 @@ __device__ inline int pack_key(float v, int mask, int idx)
     return (__float_as_int(v) & mask) | idx;
 }
 
-// fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run (best, second best) states
+// median of three; the compiler selects the single med3 instruction for this shape
+__device__ inline int med3i(int a, int b, int c) { return max(min(a, b), min(max(a, b), c)); }
+
+// insert a key into the ascending triple (m1, m2, m3) of the smallest keys seen so far
+__device__ inline void insert3(int key, int &m1, int &m2, int &m3)
+{
+    m3 = med3i(m2, m3, key);      // third smallest of {m1, m2, m3, key} given m1 <= m2 <= m3
+    m2 = med3i(m1, m2, key);      // second smallest
+    m1 = min(m1, key);
+}
+
+// fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run states: the three smallest keys.
+// The third one only serves to show that a close call is between two candidates and no more.
 template <int S, int ST>
-__device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST])
+__device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST], int (&m3)[ST])
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int k0 = pack_key(acc[4 * q + 0], mask, kidx[4 * q + 0]);
-        const int k1 = pack_key(acc[4 * q + 1], mask, kidx[4 * q + 1]);
-        const int k2 = pack_key(acc[4 * q + 2], mask, kidx[4 * q + 2]);
-        const int k3 = pack_key(acc[4 * q + 3], mask, kidx[4 * q + 3]);
-        const int lo01 = min(k0, k1), hi01 = max(k0, k1), lo23 = min(k2, k3), hi23 = max(k2, k3);
-        const int lo = min(lo01, lo23);
-        const int sec = min(min(max(lo01, lo23), hi01), hi23);        // second smallest of the four
         const int st = state_of<S>(q);
-        m2[st] = min(min(max(m1[st], lo), m2[st]), sec);
-        m1[st] = min(m1[st], lo);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) insert3(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), m1[st], m2[st], m3[st]);
     }
 }
 
-// Phase A for one wave: NB blocks of 32 points against all tiles of the group.
-// The MFMA contracts over the d centred features plus one extra pair (1, |c'|^2) x (|x'|^2, 1), so the
-// accumulator holds |x'|^2 + |c'|^2 - 2 x'.c' directly and starts from zero.  The results of one tile block
-// are folded into the running minima while the matrix unit works on the next block.
-// what phase A needs besides the tile
-struct PhaseACtx {
-    const float *xs, *mu_s, *cnmax_s;
-    const uint4 *opA_s;
-    unsigned char *labels_s, *old_s;
-    unsigned short *queue_c;
-    int *qcount_c;
+// Everything a wave needs to run its share of a chunk.  The eight waves of a workgroup share the group's
+// operand rows, centroid copy and integer accumulators (LDS), but each wave owns its points from the global
+// load to the accumulator update, so there is no barrier inside the tile loop and waves in different phases
+// (matrix pipeline / vector ALU / LDS atomics) overlap on a SIMD.
+struct WaveCtx {
+    const uint4 *opA_s;           // LDS: operand slots of the group's tiles
     const float *cs;              // the group's centroids as given (LDS copy or global), row stride cs_stride
-    int cs_stride, k0, d;
-    bool vec;                     // rows may be read 16 bytes at a time
-    unsigned char *prev_tile;     // global: previous labels, prev_tile[rl * prev_stride + p]; null when not tracked
-    int64_t prev_stride;
-    int n_tiles, n_runs_g, nvalid;
+    int cs_stride;
+    unsigned long long *sums;     // LDS: fixed-point sum deltas [row][DP + 1]
+    int *cnts;                    // LDS: member count deltas [row]
+    const float *mu_s;            // LDS: column means [32]
+    const int *shift_s;           // LDS: fixed-point shifts [32]
+    const int *wide_s;            // LDS: wide-column flags [32], any at [32]
+    const float *cnmax_s;         // LDS: per-run maximum squared norm of the centred centroids [8]
+    const float *X;               // this space's rows
+    int64_t ldx, N;
+    int d, k0, n_runs, n_tiles, grow0;
+    unsigned char *prev;          // global: labels of the last round for the group's runs, [run][N]
+    int32_t *labels_out;          // global: labels of the group's runs [run][N] (final pass) or null
+    long long *losum;             // global: low-order sums of wide columns [row][d]
+    int64_t chunk_begin, chunk_end;
+    bool vec_x, vec_c;   // vec_x / vec_c: rows of X / of the centroid copy may be read 16 bytes at a time
     float eps_a;
 };
 
-template <int DP, int S>
-__device__ inline void phase_a(const PhaseACtx &c)
+// squared distance restricted to the features [f0, f0 + nf) of a row pair, fp64 direct form
+__device__ inline double sqdist64_part(const float *x, const float *c, int nf)
 {
-    const float *xs = c.xs, *mu_s = c.mu_s;
-    const uint4 *opA_s = c.opA_s;
-    const int n_tiles = c.n_tiles;
-    constexpr int TP = tile_points_of(DP);
-    constexpr int NB = TP / (32 * kWaves);
+    double acc = 0.0;
+    for (int l = 0; l < nf; ++l) {
+        const double diff = __dsub_rn((double)x[l], (double)c[l]);
+        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
+    }
+    return acc;
+}
+
+template <int DP, int S, bool FINAL, bool TRACE>
+__device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
+{
+    constexpr int TP = tile_points_of(DP);          // points per workgroup step
+    constexpr int NB = TP / (32 * kWaves);          // blocks of 32 points per wave and step
     constexpr int H = DP / 2;                       // features per half-wave
     constexpr int NK = ksteps_of(DP);               // K-steps of 16 per cross term
     constexpr int NS = tile_slots_of(DP);           // operand slots per tile and lane
     constexpr int HP = 8 * NK;                      // feature slots per half-wave (H padded to whole K-steps)
-    constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);
-    constexpr int XS = DP + 4;
+    constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);   // runs owned by a lane
     constexpr int NM = 6 * NK + 1;                  // MFMAs per tile block
-    constexpr int VPER = (56 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
+    constexpr int VPER = (64 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
+    constexpr bool LOSS = FINAL || TRACE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hl = lane >> 5;
+    const int d = c.d;
+    const int f0 = hl * H;                          // first feature of this lane's half
+    const int nf = min(max(d - f0, 0), H);          // real features of this lane's half
+    const uint4 *opA_s = c.opA_s;
     int mask = (int)0xffffff80;
     asm volatile("" : "+v"(mask));                  // keep the mask in a VGPR
 
-    // B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
-    // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
-    bf16x8 bx[NB][3][NK], bb[NB];
-    float xn[NB];
-    int m1[NB][ST], m2[NB][ST];
-    {
-        float mu[HP];
-#pragma unroll
-        for (int s = 0; s < HP; ++s) mu[s] = s < H ? mu_s[hl * H + s] : 0.0f;
+    const bool any_wide = c.wide_s[32] != 0;
+
+    // Raw features of this lane's half of its points.  The rows of the next step are loaded while this step
+    // runs: the loads are unconditional (addresses clamped into the chunk and the row, masking happens when the
+    // values are used) and nothing touches their registers before settle(), so no wait is placed early.
+    float xnext[NB][HP];
+    auto fetch = [&](int64_t p0) {
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const int p = wave * 32 * NB + pb * 32 + n;
-            float xc[HP];
+            const int64_t p = min(p0 + wave * 32 * NB + pb * 32 + n, c.chunk_end - 1);
+            const float *row = c.X + p * c.ldx;
+            if (c.vec_x) {
 #pragma unroll
-            for (int s = 0; s < HP; ++s) xc[s] = 0.0f;
-            const float4 *row = reinterpret_cast<const float4 *>(xs + p * XS + hl * H);
+                for (int c4 = 0; c4 < H / 4; ++c4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(row + min(f0 + 4 * c4, d - 4));
+                    xnext[pb][4 * c4 + 0] = v.x; xnext[pb][4 * c4 + 1] = v.y; xnext[pb][4 * c4 + 2] = v.z; xnext[pb][4 * c4 + 3] = v.w;
+                }
+            } else {
 #pragma unroll
-            for (int c4 = 0; c4 < H / 4; ++c4) {
-                const float4 v = row[c4];
-                xc[4 * c4 + 0] = v.x - mu[4 * c4 + 0];
-                xc[4 * c4 + 1] = v.y - mu[4 * c4 + 1];
-                xc[4 * c4 + 2] = v.z - mu[4 * c4 + 2];
-                xc[4 * c4 + 3] = v.w - mu[4 * c4 + 3];
+                for (int s = 0; s < H; ++s) xnext[pb][s] = row[min(f0 + s, d - 1)];
             }
+        }
+    };
+    // the outstanding loads of fetch() have to be complete here
+    auto settle = [&]() {
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+            for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xnext[pb][s]));
+    };
+    fetch(c.chunk_begin);
+    settle();
+
+    for (int64_t p0 = c.chunk_begin; p0 < c.chunk_end; p0 += TP) {
+        float xraw[NB][HP];
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb) {
+            const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+#pragma unroll
+            for (int s = 0; s < HP; ++s) xraw[pb][s] = (s < H && s < nf && pvalid) ? xnext[pb][s] : 0.0f;
+        }
+        if (p0 + TP < c.chunk_end) fetch(p0 + TP);
+
+        // ---- B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
+        // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
+        bf16x8 bx[NB][3][NK], bb[NB];
+        float xn[NB];
+        int m1[NB][ST], m2[NB][ST], m3[NB][ST];
+        int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb) {
+            float xc[HP];
             float part = 0.0f;
 #pragma unroll
-            for (int s = 0; s < H; ++s) part = fmaf(xc[s], xc[s], part);
+            for (int s = 0; s < HP; ++s) {
+                xc[s] = s < H ? xraw[pb][s] - c.mu_s[f0 + s] : 0.0f;
+                part = fmaf(xc[s], xc[s], part);
+            }
             xn[pb] = part + __shfl_xor(part, 32, 64);
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
@@ -306,126 +386,276 @@ __device__ inline void phase_a(const PhaseACtx &c)
             unsigned nh, nm, nl;
             split3(xn[pb], nh, nm, nl);
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
+            // labels these (point, run) pairs had in the previous round, 0xff before the first one (the loads
+            // complete during the tile loop)
+            const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
 #pragma unroll
-            for (int st = 0; st < ST; ++st) { m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; }
-        }
-    }
-
-    // labels these (point, run) pairs had in the previous round (loads complete while the tiles are processed)
-    unsigned char oldl[NB][ST];
-#pragma unroll
-    for (int pb = 0; pb < NB; ++pb)
-#pragma unroll
-        for (int st = 0; st < ST; ++st) {
-            const int p = wave * 32 * NB + pb * 32 + n;
-            const int rl = S == 8 ? 0 : hl * ST + st;
-            oldl[pb][st] = (c.prev_tile && rl < c.n_runs_g && p < c.nvalid) ? c.prev_tile[rl * c.prev_stride + p] : (unsigned char)0xff;
+            for (int st = 0; st < ST; ++st) {
+                m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; m3[pb][st] = kBigKey;
+                const int rl = S == 8 ? 0 : hl * ST + st;
+                oldl[pb][st] = FINAL ? 0xff : (int)c.prev[(int64_t)min(rl, c.n_runs - 1) * c.N + min(p, c.chunk_end - 1)];
+            }
         }
 
-    // operand slots of tile t for this lane: pieces (high, middle, low) of -2c' per K-step, then the bias slot
-    bf16x8 a_cur[NS];
-    auto load_a = [&](bf16x8 (&dst)[NS], int t) {
+        // ---- distances tile by tile; the results of one block are folded while the matrix pipeline runs the next
+        bf16x8 a_cur[NS];
+        auto load_a = [&](bf16x8 (&dst)[NS], int t) {
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
-    };
-    load_a(a_cur, 0);
-
-    // results of the previous tile block, not folded yet; starts as "no result" (keys above every real key)
-    const float big = __int_as_float(kBigKey);
-    floatx16 acc_prev = {big, big, big, big, big, big, big, big, big, big, big, big, big, big, big, big};
-    int kidx_old[16];
+            for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
+        };
+        load_a(a_cur, 0);
+        const float big = __int_as_float(kBigKey);
+        floatx16 acc_prev = {big, big, big, big, big, big, big, big, big, big, big, big, big, big, big, big};
+        int kidx_old[16];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) kidx_old[e] = 0;
-
-    for (int t = 0; t < n_tiles; ++t) {
-        bf16x8 a_nxt[NS];
-        load_a(a_nxt, t + 1 < n_tiles ? t + 1 : t);
-        // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
-        int kidx[16];
+        for (int e = 0; e < 16; ++e) kidx_old[e] = 0;
+        for (int t = 0; t < c.n_tiles; ++t) {
+            bf16x8 a_nxt[NS];
+            load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
+            // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
+            int kidx[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            kidx[e] = key_index<S>(t, e >> 2, e & 3);
-            asm("" : "+s"(kidx[e]));
+            for (int e = 0; e < 16; ++e) {
+                kidx[e] = key_index<S>(t, e >> 2, e & 3);
+                asm("" : "+s"(kidx[e]));
+            }
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb) {
+                // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
+                floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // m.m
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[2 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // l.h
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][2][ks], acc, 0, 0, 0);   // h.l
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // m.h
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // h.m
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
+                if (pb == 0) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+                else fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1], m3[pb - 1]);
+#pragma unroll
+                for (int s = 0; s < NM; ++s) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);   // then a share of the fold
+                }
+                acc_prev = acc;
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
+#pragma unroll
+            for (int sl = 0; sl < NS; ++sl) a_cur[sl] = a_nxt[sl];
         }
+        fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+        // the next rows have arrived by now; asking for them here, before this step's stores are issued,
+        // keeps the (in-order) memory counter from tying the next step to those stores
+        settle();
+
+        // ---- labels, close calls, sums
+        constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
+        // Keys: which pairs does the exact arithmetic have to confirm?  pend2: against one rival (the third key
+        // is clear of the error bound), pend3: against the whole run.  Bit pb * ST + st of a lane's mask.
+        unsigned pend2 = 0, pend3 = 0;
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
-            floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // m.m
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[2 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // l.h
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][2][ks], acc, 0, 0, 0);   // h.l
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // m.h
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // h.m
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
-            if (pb == 0) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
-            else fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1]);
-#pragma unroll
-            for (int s = 0; s < NM; ++s) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);   // then a share of the fold
+            const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+            if (S == 8) {
+                // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
+                int k1 = m1[pb][0], k2 = m2[pb][0], k3 = m3[pb][0];
+                if (k1 < kBigKey) k1 |= hl << 4;
+                if (k2 < kBigKey) k2 |= hl << 4;
+                if (k3 < kBigKey) k3 |= hl << 4;
+                const int o1 = __shfl_xor(k1, 32, 64), o2 = __shfl_xor(k2, 32, 64), o3 = __shfl_xor(k3, 32, 64);
+                insert3(o1, k1, k2, k3);
+                insert3(o2, k1, k2, k3);
+                insert3(o3, k1, k2, k3);
+                m1[pb][0] = k1; m2[pb][0] = k2; m3[pb][0] = k3;
             }
-            acc_prev = acc;
-        }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
-#pragma unroll
-        for (int sl = 0; sl < NS; ++sl) a_cur[sl] = a_nxt[sl];
-    }
-    fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
-
-#pragma unroll
-    for (int pb = 0; pb < NB; ++pb) {
-        const int p = wave * 32 * NB + pb * 32 + n;
-        if (S == 8) {
-            // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
-            int k1 = m1[pb][0], k2 = m2[pb][0];
-            if (k1 < kBigKey) k1 |= hl << 4;
-            if (k2 < kBigKey) k2 |= hl << 4;
-            const int o1 = __shfl_xor(k1, 32, 64), o2 = __shfl_xor(k2, 32, 64);
-            m1[pb][0] = min(k1, o1);
-            m2[pb][0] = min(max(k1, o1), min(k2, o2));
-        }
-#pragma unroll
-        for (int st = 0; st < ST; ++st) {
-            const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
-            const bool writer = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs_g;
-            const bool active = writer && p < c.nvalid;
-            int lab = 0xff;
-            bool close = false;
-            if (active) {
-                const int k1 = m1[pb][st], k2 = m2[pb][st];
-                lab = k1 & 127;
+            for (int st = 0; st < ST; ++st) {
+                const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
+                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
+                const int k1 = m1[pb][st], k2 = m2[pb][st], k3 = m3[pb][st];
                 const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
+                const float f3 = __int_as_float(k3 & (int)0xffffff80);
                 // error bound of the expansion (rounding of norms, products and the centring) plus the
                 // 7 mantissa bits given up to the index in each key
-                const float tol = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 6.2e-5f * fabsf(f2) + 1.0e-30f;
-                close = !(f2 - f1 > tol);
+                const float tol0 = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 1.0e-30f;
+                const bool close = active && !(f2 - f1 > tol0 + 6.2e-5f * fabsf(f2));
+                const bool clear3 = f3 - f1 > tol0 + 6.2e-5f * fabsf(f3);
+                pend2 |= (unsigned)(close && clear3) << (pb * ST + st);
+                pend3 |= (unsigned)(close && !clear3) << (pb * ST + st);
             }
-            // too close to call: the wave decides these pairs one after the other with the exact arithmetic
-            unsigned long long todo = __ballot(close);
+        }
+
+        // A close call between exactly two centroids is decided by the lane pair of the point with the exact
+        // arithmetic: the lower half-wave sums its features in fp64, the upper one continues the same sum with
+        // its features - the order of the plain loop over all features - and compares.  One pair per pass.
+        {
+            const unsigned other2 = __shfl_xor(pend2, 32, 64);
+            unsigned both = hl ? (other2 | (pend2 << NBST)) : (pend2 | (other2 << NBST));
+            while (__ballot(both != 0u) != 0ull) {
+                const bool act = both != 0u;
+                const int bit = act ? __ffs(both) - 1 : 0;
+                both &= both - 1u;
+                const int oh = bit / NBST, idx = bit % NBST, pb = idx / ST, st = idx % ST;
+                int kk = 0;                         // the owner's two candidates
+#pragma unroll
+                for (int i = 0; i < NBST; ++i)
+                    if (i == idx) kk = (m1[i / ST][i % ST] & 127) | ((m2[i / ST][i % ST] & 127) << 8);
+                const int kko = __shfl_xor(kk, 32, 64);
+                if (hl != oh) kk = kko;
+                const int j1 = kk & 0xff, j2 = kk >> 8;
+                const int rl = S == 8 ? 0 : oh * ST + st;
+                const float *crun = c.cs + (rl * c.k0 + rl * (rl - 1) / 2) * c.cs_stride + f0;
+                float xs[H];
+#pragma unroll
+                for (int s = 0; s < H; ++s) {
+                    xs[s] = xraw[0][s];
+#pragma unroll
+                    for (int q = 1; q < NB; ++q)
+                        if (pb == q) xs[s] = xraw[q][s];
+                }
+                float c1[H], c2[H];
+                load_half_row<H>(c1, crun + j1 * c.cs_stride, nf, c.vec_c);
+                load_half_row<H>(c2, crun + j2 * c.cs_stride, nf, c.vec_c);
+                double d1 = 0.0, d2 = 0.0;
+                if (hl == 0) { d1 = sqdist64_cont<H>(0.0, xs, c1, nf); d2 = sqdist64_cont<H>(0.0, xs, c2, nf); }
+                const double u1 = __shfl_xor(d1, 32, 64), u2 = __shfl_xor(d2, 32, 64);
+                int win = j1;
+                if (hl == 1) {
+                    d1 = sqdist64_cont<H>(u1, xs, c1, nf); d2 = sqdist64_cont<H>(u2, xs, c2, nf);
+                    win = (d2 < d1 || (d2 == d1 && j2 < j1)) ? j2 : j1;
+                }
+                const int wino = __shfl_xor(win, 32, 64);
+                if (hl == 0) win = wino;
+                if (act && hl == oh) {
+#pragma unroll
+                    for (int i = 0; i < NBST; ++i)
+                        if (i == idx) m1[i / ST][i % ST] = win;
+                }
+            }
+        }
+        // Three or more candidates (exact ties on integer data, duplicate centroids): the whole wave scans the run.
+        {
+            unsigned long long todo = __ballot(pend3 != 0u);
             while (todo) {
                 const int src = __ffsll((long long)todo) - 1;
-                todo &= todo - 1;
-                const int sp = wave * 32 * NB + pb * 32 + (src & 31);
+                const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend3, src);
+                const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
+                const int64_t sp = p0 + wave * 32 * NB + pb * 32 + (src & 31);
                 const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
                 const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * c.cs_stride;
-                const int arg = exact_argmin_wave(xs + sp * XS, crun, c.cs_stride, c.k0 + srl, c.d, c.vec);
-                if (lane == src) lab = arg;
+                const int arg = exact_argmin_wave(c.X + sp * c.ldx, crun, c.cs_stride, c.k0 + srl, d, c.vec_x && c.vec_c);
+                if (lane == src) {
+                    pend3 &= pend3 - 1u;
+#pragma unroll
+                    for (int i = 0; i < NBST; ++i)
+                        if (i == idx) m1[i / ST][i % ST] = arg;
+                }
+                todo = __ballot(pend3 != 0u);
             }
-            if (active && c.prev_tile && lab != (int)oldl[pb][st]) {
-                const int slot = atomicAdd(c.qcount_c, 1);
-                c.queue_c[slot] = (unsigned short)(p | (rl << 9));
-                c.old_s[p * 8 + rl] = oldl[pb][st];
-                c.prev_tile[rl * c.prev_stride + p] = (unsigned char)lab;
+        }
+
+        // labels are final: output, and which pairs moved
+        unsigned mv = 0;
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb) {
+            const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
+#pragma unroll
+            for (int st = 0; st < ST; ++st) {
+                const int rl = S == 8 ? 0 : hl * ST + st;
+                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
+                const int lab = m1[pb][st] & 127;
+                if (FINAL) {
+                    if (active && c.labels_out) c.labels_out[(int64_t)rl * c.N + p] = lab;
+                } else {
+                    const bool moved = active && lab != oldl[pb][st];
+                    if (moved) c.prev[(int64_t)rl * c.N + p] = (unsigned char)lab;
+                    mv |= (unsigned)moved << (pb * ST + st);
+                }
             }
-            if (writer) c.labels_s[p * 8 + rl] = (unsigned char)lab;
+        }
+
+        if (!FINAL) {
+            // Exact sums: a point whose label changed moves its fixed-point row from the old cluster to the new
+            // one.  Both lanes of the point's pair take part (each holds half of the features); one pair per pass.
+            const unsigned mvo = __shfl_xor(mv, 32, 64);
+            unsigned both = hl ? (mvo | (mv << NBST)) : (mv | (mvo << NBST));
+            while (__ballot(both != 0u) != 0ull) {
+                const bool act = both != 0u;
+                const int bit = act ? __ffs(both) - 1 : 0;
+                both &= both - 1u;
+                const int oh = bit / NBST, idx = bit % NBST, pb = idx / ST, st = idx % ST;
+                int kk = 0;                         // the owner's (old << 8) | new
+#pragma unroll
+                for (int i = 0; i < NBST; ++i)
+                    if (i == idx) kk = (m1[i / ST][i % ST] & 127) | (oldl[i / ST][i % ST] << 8);
+                const int kko = __shfl_xor(kk, 32, 64);
+                if (hl != oh) kk = kko;
+                const int nl = kk & 0xff, ol = kk >> 8;
+                const int r = S == 8 ? 0 : oh * ST + st;
+                const int rowbase = r * c.k0 + r * (r - 1) / 2;
+                if (act) {
+                    unsigned long long *so = c.sums + (rowbase + ol) * (DP + 1) + f0;
+                    unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+#pragma unroll
+                    for (int s = 0; s < H; ++s) {
+                        float xv = xraw[0][s];
+#pragma unroll
+                        for (int q = 1; q < NB; ++q)
+                            if (pb == q) xv = xraw[q][s];
+                        if (s < nf) {
+                            const long long fx = to_fixed(xv, c.shift_s[f0 + s]);
+                            if (ol != 0xff) atomicAdd(so + s, (unsigned long long)(-fx));
+                            atomicAdd(sn + s, (unsigned long long)fx);
+                        }
+                    }
+                    if (hl == 0) {
+                        if (ol != 0xff) atomicAdd(&c.cnts[rowbase + ol], -1);
+                        atomicAdd(&c.cnts[rowbase + nl], 1);
+                    }
+                    if (any_wide) {
+                        // rare: bits below the grid of a wide column go to a global integer accumulator
+                        const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
+                        const int64_t crow = c.grow0 + rowbase;
+                        for (int s = 0; s < nf; ++s) {
+                            if (c.wide_s[f0 + s] == 0) continue;
+                            const long long lo = fixed_low(c.X[p * c.ldx + f0 + s], c.shift_s[f0 + s]);
+                            if (lo == 0) continue;
+                            if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + f0 + s]), (unsigned long long)(-lo));
+                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + f0 + s]), (unsigned long long)lo);
+                        }
+                    }
+                }
+            }
+        }
+        if (LOSS) {
+            // loss of this assignment: each half-wave sums its features in fp64, the pair adds up
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb) {
+                const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+                for (int r = 0; r < c.n_runs; ++r) {
+                    const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
+                    int lab = 0;
+#pragma unroll
+                    for (int st = 0; st < ST; ++st)
+                        if (st == ost) lab = m1[pb][st] & 127;
+                    const int labo = __shfl_xor(lab, 32, 64);
+                    if (hl != oh) lab = labo;
+                    double part = 0.0;
+                    if (pvalid) {
+                        const int lrow = r * c.k0 + r * (r - 1) / 2 + lab;
+                        part = sqdist64_part(xraw[pb], c.cs + lrow * c.cs_stride + f0, nf);
+                    }
+                    const double sum = __dadd_rn(part, __shfl_xor(part, 32, 64));
+                    if (hl == 0) jloc[r] = __dadd_rn(jloc[r], sum);
+                }
+            }
         }
     }
 }
@@ -433,16 +663,6 @@ __device__ inline void phase_a(const PhaseACtx &c)
 template <int DP, bool FINAL, bool TRACE>
 __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, StepArgs a)
 {
-    constexpr int TP = tile_points_of(DP);
-    constexpr int XS = DP + 4;
-    constexpr int PPP = kThreads / DP;            // points per pass of the (point, feature) mapping
-    constexpr int NQ = TP / PPP;                  // passes per tile
-    constexpr int TPP = DP / 4;                   // threads per point of the (point, 4 features) mapping
-    constexpr int PPP4 = kThreads / TPP;          // points per pass of that mapping
-    constexpr int NQ4 = TP / PPP4;                // passes per tile
-    constexpr int RSTEP = kThreads / TP;          // runs covered per pass of the (point, run) mapping: 1 or 2
-    constexpr int NR = 8 / RSTEP;                 // passes of the (point, run) mapping
-    constexpr bool LOSS = FINAL || TRACE;
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int b = blockIdx.y;
@@ -454,30 +674,22 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     const int k0 = plan.k_min + g.run0;                                   // k of the group's first run
     const int grow0 = rows_before(plan.k_min, g.run0);                    // first centroid row of the group
     const int real_rows = rows_before(plan.k_min, g.run0 + g.n_runs) - grow0;
-    const Carve cv = carve_lds(DP, d, g.n_tiles, real_rows, g.cs_lds != 0);
+    const Carve cv = carve_lds(DP, d, g.n_tiles, real_rows);
 
-    float *xs = reinterpret_cast<float *>(smem + cv.xs);
     uint4 *opA_s = reinterpret_cast<uint4 *>(smem + cv.opA);
     float *cs_lds = reinterpret_cast<float *>(smem + cv.cs);
     unsigned long long *sums = reinterpret_cast<unsigned long long *>(smem + cv.sums);
     int *cnts = reinterpret_cast<int *>(smem + cv.cnts);
-    unsigned char *labels_s = smem + cv.labels;
-    unsigned char *old_s = smem + cv.old;
-    unsigned short *queue_c = reinterpret_cast<unsigned short *>(smem + cv.queue_c);
     float *mu_s = reinterpret_cast<float *>(smem + cv.misc);              // [32]
     int *shift_s = reinterpret_cast<int *>(smem + cv.misc + 128);         // [32]
     int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
     float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
-    int *qcount_c = reinterpret_cast<int *>(smem + cv.misc + 436);
     double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][kWaves]
 
     const int tid = threadIdx.x;
     char *wsb = a.ws + (int64_t)b * a.ws_bs;
     const float *Xb = a.X + (int64_t)b * a.x_bs;
     const float *Cb = a.C + (int64_t)b * a.c_bs;
-    unsigned char *prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev);   // [n_runs][N] labels of the last round
-    const bool first_round = a.first_round != 0;
-    const bool track = !FINAL && !first_round;      // compare with, and update, the previous labels point by point
 
     // group operands, centroids and column info into LDS; accumulators to zero
     {
@@ -488,7 +700,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         if (tid < 33) wide_s[tid] = colwide[tid];
         const uint4 *src = reinterpret_cast<const uint4 *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
         for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
-        if (g.cs_lds) {
+        {
             const float *csrc = Cb + (int64_t)grow0 * d;
             for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[(e / d) * (d + 4) + e % d] = csrc[e];
         }
@@ -497,165 +709,49 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
             for (int e = tid; e < real_rows * (DP + 1); e += kThreads) sums[e] = 0ull;
             for (int e = tid; e < real_rows; e += kThreads) cnts[e] = 0;
         }
-        if (tid == 0) *qcount_c = 0;
     }
     __syncthreads();
 
-    // the group's centroids as given: the LDS copy, or global memory when the copy did not fit
-    const float *cs = g.cs_lds ? cs_lds : Cb + (int64_t)grow0 * d;
-    const int cs_stride = g.cs_lds ? d + 4 : d;
-    const int l = tid % DP, pg = tid / DP;                           // (point, feature) mapping
-    const int l4 = (tid % TPP) * 4, pg4 = tid / TPP;                 // (point, 4 features) mapping
-    const int my_shift = shift_s[l];
-    const bool any_wide = wide_s[32] != 0;
-    const bool my_wide = wide_s[l] != 0;
-    // bound on the error of phase A's distances relative to |x'|^2 + |c'|^2: dropped piece products (2^-23), seven
-    // chained fp32 accumulations of up to 16 products each, rounding of the norms and of the centring
-    const float eps_a = (float)(8 * (DP + 8)) * 1.1920928955078125e-07f;   // 8 (DP + 8) 2^-23
-    const int pr_p = tid % TP;                                       // (point, run) mapping: this thread's point
+    WaveCtx c;
+    c.opA_s = opA_s;
+    c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
+    c.cs_stride = d + 4;
+    c.sums = sums; c.cnts = cnts; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
+    c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
+    c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
+    c.labels_out = (FINAL && a.labels) ? a.labels + (int64_t)b * a.lab_bs + (int64_t)g.run0 * a.N : nullptr;
+    c.losum = reinterpret_cast<long long *>(wsb + a.off_losum);
+    c.chunk_begin = (int64_t)chunk * plan.chunk_len;
+    c.chunk_end = min(a.N, c.chunk_begin + plan.chunk_len);
     // 16-byte loads need whole quads of features and aligned rows
-    const bool vec_ok = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
+    c.vec_x = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
+    c.vec_c = d % 4 == 0;
+    // bound on the error of the matrix-pipeline distances relative to |x'|^2 + |c'|^2: dropped piece products
+    // (2^-23), seven chained fp32 accumulations of up to 16 products each, rounding of the norms and of the centring
+    c.eps_a = (float)(8 * (DP + 8)) * 1.1920928955078125e-07f;   // 8 (DP + 8) 2^-23
 
-    double jloc[NR];
+    double jloc[8];
 #pragma unroll
-    for (int i = 0; i < NR; ++i) jloc[i] = 0.0;
+    for (int i = 0; i < 8; ++i) jloc[i] = 0.0;
 
-    const int64_t chunk_begin = (int64_t)chunk * plan.chunk_len;
-    const int64_t chunk_end = min(a.N, chunk_begin + plan.chunk_len);
-
-    // raw rows of the next tile travel in registers while the current tile is processed
-    float4 xr[NQ4];
-    auto fetch_tile = [&](int64_t pt) {
-        const int nv = (int)max((int64_t)0, min((int64_t)TP, chunk_end - pt));
-#pragma unroll
-        for (int i = 0; i < NQ4; ++i) {
-            const int p = pg4 + PPP4 * i;
-            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (p < nv) {
-                const float *row = Xb + (pt + p) * a.ldx;
-                if (vec_ok) {
-                    if (l4 < d) v = *reinterpret_cast<const float4 *>(row + l4);
-                } else {
-                    if (l4 + 0 < d) v.x = row[l4 + 0];
-                    if (l4 + 1 < d) v.y = row[l4 + 1];
-                    if (l4 + 2 < d) v.z = row[l4 + 2];
-                    if (l4 + 3 < d) v.w = row[l4 + 3];
-                }
-            }
-            xr[i] = v;
-        }
-    };
-    fetch_tile(chunk_begin);
-
-    PhaseACtx ctx;
-    ctx.xs = xs; ctx.opA_s = opA_s; ctx.mu_s = mu_s; ctx.cnmax_s = cnmax_s;
-    ctx.labels_s = labels_s; ctx.old_s = old_s; ctx.queue_c = queue_c; ctx.qcount_c = qcount_c;
-    ctx.cs = cs; ctx.cs_stride = cs_stride; ctx.k0 = k0; ctx.d = d;
-    // 16-byte reads of centroid rows: LDS copy (padded stride) or global rows, both with d a multiple of 4
-    ctx.vec = (d % 4 == 0) && (g.cs_lds || (reinterpret_cast<uintptr_t>(cs) & 15) == 0);
-    ctx.prev_stride = a.N; ctx.n_tiles = g.n_tiles; ctx.n_runs_g = g.n_runs; ctx.eps_a = eps_a;
-
-    for (int64_t p0 = chunk_begin; p0 < chunk_end; p0 += TP) {
-        const int nvalid = (int)min((int64_t)TP, chunk_end - p0);
-        // ---- phase 0: tile into LDS; start the loads of the next tile
-#pragma unroll
-        for (int i = 0; i < NQ4; ++i) *reinterpret_cast<float4 *>(xs + (pg4 + PPP4 * i) * XS + l4) = xr[i];
-        fetch_tile(p0 + TP);
-        __syncthreads();
-
-        // ---- phase A (the lanes that own a (point, run) result also settle close calls and compare the label
-        //      with the one of the previous round)
-        ctx.nvalid = nvalid;
-        ctx.prev_tile = track ? prev + (int64_t)g.run0 * a.N + p0 : nullptr;
-        switch (g.S) {
-        case 1: phase_a<DP, 1>(ctx); break;
-        case 2: phase_a<DP, 2>(ctx); break;
-        case 4: phase_a<DP, 4>(ctx); break;
-        default: phase_a<DP, 8>(ctx); break;
-        }
-        __syncthreads();
-
-        // ---- phase C: exact sums
-        if (!FINAL) {
-            long long *losum = reinterpret_cast<long long *>(wsb + a.off_losum);
-            if (first_round) {
-                // every point joins a cluster: dense pass, no queue
-#pragma unroll
-                for (int i = 0; i < NR; ++i) {
-                    const int rl = tid / TP + RSTEP * i;
-                    if (rl < g.n_runs && pr_p < nvalid) {
-                        const int j = labels_s[pr_p * 8 + rl];
-                        atomicAdd(&cnts[rl * k0 + rl * (rl - 1) / 2 + j], 1);
-                        prev[(int64_t)(g.run0 + rl) * a.N + p0 + pr_p] = (unsigned char)j;
-                    }
-                }
-                if (l < d) {
-                    for (int i = 0; i < NQ; ++i) {
-                        const int p = pg + PPP * i;
-                        if (p < nvalid) {
-                            const float x = xs[p * XS + l];
-                            const unsigned long long q = (unsigned long long)to_fixed(x, my_shift);
-                            const long long lo = (any_wide && my_wide) ? fixed_low(x, my_shift) : 0;
-                            const uint2 lab8 = *reinterpret_cast<const uint2 *>(labels_s + p * 8);
-                            int rowbase = 0;
-                            for (int rl = 0; rl < g.n_runs; ++rl) {
-                                const unsigned w = rl < 4 ? lab8.x : lab8.y;
-                                const int row = rowbase + (int)((w >> (8 * (rl & 3))) & 0xffu);
-                                atomicAdd(&sums[row * (DP + 1) + l], q);
-                                if (lo != 0) atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(int64_t)(grow0 + row) * d + l]), (unsigned long long)lo);
-                                rowbase += k0 + rl;
-                            }
-                        }
-                    }
-                }
-            } else {
-                // move the rows of points whose label changed from the old cluster's sums to the new one's
-                const int nq = *qcount_c;
-                for (int e = pg; e < nq; e += PPP) {
-                    const int ent = queue_c[e];
-                    const int p = ent & 511, rl = ent >> 9;
-                    const int ol = old_s[p * 8 + rl], nl = labels_s[p * 8 + rl];
-                    const int rowbase = rl * k0 + rl * (rl - 1) / 2;
-                    if (l < d) {
-                        const float x = xs[p * XS + l];
-                        const long long q = to_fixed(x, my_shift);
-                        if (ol != 0xff) atomicAdd(&sums[(rowbase + ol) * (DP + 1) + l], (unsigned long long)(-q));
-                        atomicAdd(&sums[(rowbase + nl) * (DP + 1) + l], (unsigned long long)q);
-                        if (any_wide && my_wide) {
-                            // rare: bits below the column grid go to a global integer accumulator
-                            const long long lo = fixed_low(x, my_shift);
-                            if (lo != 0) {
-                                const int64_t crow = grow0 + rowbase;
-                                if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(crow + ol) * d + l]), (unsigned long long)(-lo));
-                                atomicAdd(reinterpret_cast<unsigned long long *>(&losum[(crow + nl) * d + l]), (unsigned long long)lo);
-                            }
-                        }
-                    }
-                    if (l == 0) {
-                        if (ol != 0xff) atomicAdd(&cnts[rowbase + ol], -1);
-                        atomicAdd(&cnts[rowbase + nl], 1);
-                    }
-                }
-            }
-        }
-
-        // ---- loss of this assignment (fp64, direct form) and label output
-        if (LOSS) {
-#pragma unroll
-            for (int i = 0; i < NR; ++i) {
-                const int rl = tid / TP + RSTEP * i;
-                if (rl < g.n_runs && pr_p < nvalid) {
-                    const int j = labels_s[pr_p * 8 + rl];
-                    const int lrow = rl * k0 + rl * (rl - 1) / 2 + j;
-                    jloc[i] = __dadd_rn(jloc[i], sqdist64(xs + pr_p * XS, cs + lrow * cs_stride, d));
-                    if (FINAL && a.labels)
-                        a.labels[(int64_t)b * a.lab_bs + (int64_t)(g.run0 + rl) * a.N + p0 + pr_p] = j;
-                }
-            }
-        }
-        __syncthreads();
-        if (tid == 0) *qcount_c = 0;
+    if (c.chunk_begin < c.chunk_end) switch (g.S) {
+    case 1: wave_loop<DP, 1, FINAL, TRACE>(c, jloc); break;
+    case 2: wave_loop<DP, 2, FINAL, TRACE>(c, jloc); break;
+    case 4: wave_loop<DP, 4, FINAL, TRACE>(c, jloc); break;
+    default: wave_loop<DP, 8, FINAL, TRACE>(c, jloc); break;
     }
+
+    if (FINAL || TRACE) {
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            double v = jloc[i];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v = __dadd_rn(v, __shfl_xor(v, off, 64));
+            if (lane == 0) jpart[i * kWaves + wave] = v;
+        }
+    }
+    __syncthreads();   // every wave has finished its points: accumulators and partial losses are complete
 
     if (!FINAL) {
         unsigned long long *psum = reinterpret_cast<unsigned long long *>(wsb + a.off_psum) +
@@ -664,22 +760,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         int *pcnt = reinterpret_cast<int *>(wsb + a.off_pcnt) + (int64_t)chunk * plan.total_rows + grow0;
         for (int e = tid; e < real_rows; e += kThreads) pcnt[e] = cnts[e];
     }
-    if (LOSS) {
-        const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-        for (int i = 0; i < NR; ++i) {
-            double v = jloc[i];
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v = __dadd_rn(v, __shfl_xor(v, off, 64));
-            if (lane == 0) jpart[i * kWaves + wave] = v;
-        }
-        __syncthreads();
+    if (FINAL || TRACE) {
         if (tid < g.n_runs) {
-            // run rl was covered by pass rl / RSTEP of the waves whose threads have tid / TP == rl % RSTEP
-            const int rl = tid, i = rl / RSTEP, w0 = (rl % RSTEP) * (kWaves / RSTEP);
             double v = 0.0;
-            for (int w = 0; w < kWaves / RSTEP; ++w) v = __dadd_rn(v, jpart[i * kWaves + w0 + w]);
-            reinterpret_cast<double *>(wsb + a.off_pj)[(int64_t)chunk * plan.n_runs + g.run0 + rl] = v;
+            for (int w = 0; w < kWaves; ++w) v = __dadd_rn(v, jpart[tid * kWaves + w]);
+            reinterpret_cast<double *>(wsb + a.off_pj)[(int64_t)chunk * plan.n_runs + g.run0 + tid] = v;
         }
     }
 }
@@ -1046,14 +1131,13 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     for (int gi = 0; gi < plan.n_groups; ++gi) {
         const GroupDesc &g = plan.g[gi];
         const int rr = rows_before(plan.k_min, g.run0 + g.n_runs) - rows_before(plan.k_min, g.run0);
-        const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr, g.cs_lds != 0).total;
+        const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr).total;
         if (need > lds) lds = need;
     }
     const dim3 grid(plan.n_groups * plan.n_chunks, batch);
     const bool trace = a.trace != nullptr;
     const bool prof = profile_enabled();
     for (int t = 0; t < a.iters; ++t) {
-        sa.first_round = t == 0 ? 1 : 0;
         if (prof) { hipError_t e = profile_mark(s, true); if (e != hipSuccess) return e; }
         if (trace) {
             hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(kThreads), lds, s, plan, sa);
@@ -1066,7 +1150,6 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         }
         hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
     }
-    sa.first_round = 0;
     hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false>), grid, dim3(kThreads), lds, s, plan, sa);
     hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws, L.per_batch,
                        L.pj, a.inertia, (int64_t)plan.n_runs, (int64_t)1, (int64_t)0);
@@ -1090,9 +1173,9 @@ LloydGeometry lloyd_geometry(int dp)
     return g;
 }
 
-int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, bool with_cs)
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows)
 {
-    return carve_lds(dp, d, n_tiles, real_rows, with_cs).total;
+    return carve_lds(dp, d, n_tiles, real_rows).total;
 }
 
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan)
@@ -1106,10 +1189,9 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
     int tiles = 0;
     int run = 0;
     while (run < plan->n_runs) {
-        // candidates: R runs side by side (8 / R slots each), with or without the LDS copy of the centroids;
-        // take the one with the least padding per real row, preferring the copy and then the larger R
+        // candidates: R runs side by side (8 / R slots each); take the one with the least padding per real
+        // row, preferring the larger R
         int best_R = 0, best_tiles = 0, best_nr = 0;
-        bool best_cs = false;
         double best_score = 1e30;
         for (int R = 8; R >= 1; R >>= 1) {
             const int S = 8 / R;
@@ -1119,20 +1201,17 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
             const int n_tiles = (quads + S - 1) / S;
             const int real_rows = rows_before(k_min, run + nr) - rows_before(k_min, run);
             if (n_tiles > 32) continue;
-            for (int with_cs = 1; with_cs >= 0; --with_cs) {
-                if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows, with_cs != 0) > geo.lds_budget) continue;
-                // cost per real row: padded rows, a fixed per-group overhead, and a small penalty for the missing copy
-                const double score = (n_tiles * 32.0 + 24.0) / real_rows + (with_cs ? 0.0 : 0.02);
-                if (score < best_score - 1e-12) {
-                    best_score = score; best_R = R; best_tiles = n_tiles; best_nr = nr; best_cs = with_cs != 0;
-                }
-                break;
+            if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows) > geo.lds_budget) continue;
+            // cost per real row: padded rows and a fixed per-group overhead
+            const double score = (n_tiles * 32.0 + 24.0) / real_rows;
+            if (score < best_score - 1e-12) {
+                best_score = score; best_R = R; best_tiles = n_tiles; best_nr = nr;
             }
         }
         if (best_R == 0 || plan->n_groups >= kMaxGroups) return RLS_ERR_INVALID_ARG;
         GroupDesc &g = plan->g[plan->n_groups++];
         g.run0 = (int16_t)run; g.n_runs = (int16_t)best_nr; g.S = (int16_t)(8 / best_R); g.n_tiles = (int16_t)best_tiles;
-        g.cs_lds = best_cs ? 1 : 0; g.pad = 0; g.tile0 = tiles;
+        g.pad0 = 0; g.pad = 0; g.tile0 = tiles;
         tiles += best_tiles;
         run += best_nr;
     }

@@ -34,7 +34,7 @@ struct GroupDesc {
     int16_t n_runs;    // real runs in this group (<= 8 / S)
     int16_t S;         // slots per run: 1, 2, 4 or 8
     int16_t n_tiles;   // 32-row tiles
-    int16_t cs_lds;    // 1: the group's centroids (as given) are also copied to LDS
+    int16_t pad0;
     int16_t pad;
     int32_t tile0;     // tiles of all earlier groups (offset of this group's operand block)
 };
@@ -65,8 +65,8 @@ struct LloydGeometry {
 };
 LloydGeometry lloyd_geometry(int dp);
 int padded_d(int d);
-// LDS bytes of a group: fixed part + operand tiles + exact-sum accumulators
-int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, bool with_cs);
+// LDS bytes of a group: operand tiles + centroid copy + exact-sum accumulators + fixed part
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows);
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan);
 
 // Workspace carving for one sweep (all offsets in bytes from the workspace base, per batch element
