@@ -79,18 +79,12 @@ struct StepArgs {
 __device__ inline long long to_fixed(float x, int shift)
 {
     const unsigned u = __float_as_uint(x);
-    int e = (int)((u >> 23) & 0xffu);
-    unsigned m = u & 0x7fffffu;
-    if (e == 0) {
-        if (m == 0) return 0;
-        e = 1;
-    } else {
-        m |= 0x800000u;
-    }
-    const int sh = e - 150 + shift;
-    long long q;
-    if (sh >= 0) q = (long long)m << (sh > 39 ? 39 : sh);
-    else q = (long long)(m >> (-sh > 31 ? 31 : -sh));
+    const int e0 = (int)((u >> 23) & 0xffu);
+    const unsigned m = (u & 0x7fffffu) | (e0 ? 0x800000u : 0u);      // subnormals: no hidden bit, exponent 1
+    const int sh = (e0 ? e0 : 1) - 150 + shift;
+    const long long up = (long long)m << min(max(sh, 0), 39);
+    const long long down = (long long)(m >> min(max(-sh, 0), 31));
+    const long long q = sh >= 0 ? up : down;
     return (u >> 31) ? -q : q;
 }
 
@@ -143,6 +137,20 @@ __device__ inline double sqdist64_v4(const float *x, const float *c, int d)
         acc = __dadd_rn(acc, __dmul_rn(diff, diff));
     }
     return acc;
+}
+
+// value of the lane 32 places away (the other half-wave), by a register swap: no trip through LDS
+__device__ inline int xchg32(int v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)((threadIdx.x & 32) ? r[0] : r[1]);
+}
+__device__ inline unsigned xchg32(unsigned v) { return (unsigned)xchg32((int)v); }
+__device__ inline float xchg32(float v) { return __int_as_float(xchg32(__float_as_int(v))); }
+__device__ inline double xchg32(double v)
+{
+    const int lo = xchg32(__double2loint(v)), hi = xchg32(__double2hiint(v));
+    return __hiloint2double(hi, lo);
 }
 
 // half of a centroid row (the features of one half-wave) from LDS into registers
@@ -278,6 +286,7 @@ struct WaveCtx {
     int32_t *labels_out;          // global: labels of the group's runs [run][N] (final pass) or null
     long long *losum;             // global: low-order sums of wide columns [row][d]
     int64_t chunk_begin, chunk_end;
+    int *next_slab;               // LDS: next slab of the chunk to hand out
     bool vec_x, vec_c;   // vec_x / vec_c: rows of X / of the centroid copy may be read 16 bytes at a time
     float eps_a;
 };
@@ -324,7 +333,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     auto fetch = [&](int64_t p0) {
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const int64_t p = min(p0 + wave * 32 * NB + pb * 32 + n, c.chunk_end - 1);
+            const int64_t p = min(p0 + pb * 32 + n, c.chunk_end - 1);
             const float *row = c.X + p * c.ldx;
             if (c.vec_x) {
 #pragma unroll
@@ -345,18 +354,32 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
             for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xnext[pb][s]));
     };
-    fetch(c.chunk_begin);
+    // The chunk is handed out in slabs of SLAB points: the first eight statically, the rest from a counter in
+    // LDS, so the waves of the workgroup finish together however their close calls and updates are spread.
+    constexpr int SLAB = 32 * NB;
+    const int n_slabs = (int)((c.chunk_end - c.chunk_begin + SLAB - 1) / SLAB);
+    auto grab = [&]() -> int {
+        int v = 0;
+        if (lane == 0) v = atomicAdd(c.next_slab, 1);
+        return __builtin_amdgcn_readfirstlane(v);
+    };
+    int cur = wave;
+    if (cur >= n_slabs) return;
+    fetch(c.chunk_begin + (int64_t)cur * SLAB);
     settle();
+    int nxt = grab();
 
-    for (int64_t p0 = c.chunk_begin; p0 < c.chunk_end; p0 += TP) {
+    while (cur < n_slabs) {
+        const int64_t base = c.chunk_begin + (int64_t)cur * SLAB;     // first point of this wave's slab
         float xraw[NB][HP];
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+            const bool pvalid = base + pb * 32 + n < c.chunk_end;
 #pragma unroll
             for (int s = 0; s < HP; ++s) xraw[pb][s] = (s < H && s < nf && pvalid) ? xnext[pb][s] : 0.0f;
         }
-        if (p0 + TP < c.chunk_end) fetch(p0 + TP);
+        if (nxt < n_slabs) fetch(c.chunk_begin + (int64_t)nxt * SLAB);
+        const int nxt2 = grab();
 
         // ---- B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
         // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
@@ -373,7 +396,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 xc[s] = s < H ? xraw[pb][s] - c.mu_s[f0 + s] : 0.0f;
                 part = fmaf(xc[s], xc[s], part);
             }
-            xn[pb] = part + __shfl_xor(part, 32, 64);
+            xn[pb] = part + xchg32(part);
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
                 unsigned ph[8], pm[8], pl[8];
@@ -388,7 +411,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
             // labels these (point, run) pairs had in the previous round, 0xff before the first one (the loads
             // complete during the tile loop)
-            const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
+            const int64_t p = base + pb * 32 + n;
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; m3[pb][st] = kBigKey;
@@ -454,6 +477,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         // the next rows have arrived by now; asking for them here, before this step's stores are issued,
         // keeps the (in-order) memory counter from tying the next step to those stores
         settle();
+        if (!FINAL) {
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int st = 0; st < ST; ++st) asm volatile("" : "+v"(oldl[pb][st]));
+        }
 
         // ---- labels, close calls, sums
         constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
@@ -462,14 +491,14 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         unsigned pend2 = 0, pend3 = 0;
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+            const bool pvalid = base + pb * 32 + n < c.chunk_end;
             if (S == 8) {
                 // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
                 int k1 = m1[pb][0], k2 = m2[pb][0], k3 = m3[pb][0];
                 if (k1 < kBigKey) k1 |= hl << 4;
                 if (k2 < kBigKey) k2 |= hl << 4;
                 if (k3 < kBigKey) k3 |= hl << 4;
-                const int o1 = __shfl_xor(k1, 32, 64), o2 = __shfl_xor(k2, 32, 64), o3 = __shfl_xor(k3, 32, 64);
+                const int o1 = xchg32(k1), o2 = xchg32(k2), o3 = xchg32(k3);
                 insert3(o1, k1, k2, k3);
                 insert3(o2, k1, k2, k3);
                 insert3(o3, k1, k2, k3);
@@ -496,7 +525,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         // arithmetic: the lower half-wave sums its features in fp64, the upper one continues the same sum with
         // its features - the order of the plain loop over all features - and compares.  One pair per pass.
         {
-            const unsigned other2 = __shfl_xor(pend2, 32, 64);
+            const unsigned other2 = xchg32(pend2);
             unsigned both = hl ? (other2 | (pend2 << NBST)) : (pend2 | (other2 << NBST));
             while (__ballot(both != 0u) != 0ull) {
                 const bool act = both != 0u;
@@ -507,7 +536,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int i = 0; i < NBST; ++i)
                     if (i == idx) kk = (m1[i / ST][i % ST] & 127) | ((m2[i / ST][i % ST] & 127) << 8);
-                const int kko = __shfl_xor(kk, 32, 64);
+                const int kko = xchg32(kk);
                 if (hl != oh) kk = kko;
                 const int j1 = kk & 0xff, j2 = kk >> 8;
                 const int rl = S == 8 ? 0 : oh * ST + st;
@@ -525,13 +554,13 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 load_half_row<H>(c2, crun + j2 * c.cs_stride, nf, c.vec_c);
                 double d1 = 0.0, d2 = 0.0;
                 if (hl == 0) { d1 = sqdist64_cont<H>(0.0, xs, c1, nf); d2 = sqdist64_cont<H>(0.0, xs, c2, nf); }
-                const double u1 = __shfl_xor(d1, 32, 64), u2 = __shfl_xor(d2, 32, 64);
+                const double u1 = xchg32(d1), u2 = xchg32(d2);
                 int win = j1;
                 if (hl == 1) {
                     d1 = sqdist64_cont<H>(u1, xs, c1, nf); d2 = sqdist64_cont<H>(u2, xs, c2, nf);
                     win = (d2 < d1 || (d2 == d1 && j2 < j1)) ? j2 : j1;
                 }
-                const int wino = __shfl_xor(win, 32, 64);
+                const int wino = xchg32(win);
                 if (hl == 0) win = wino;
                 if (act && hl == oh) {
 #pragma unroll
@@ -547,7 +576,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const int src = __ffsll((long long)todo) - 1;
                 const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend3, src);
                 const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
-                const int64_t sp = p0 + wave * 32 * NB + pb * 32 + (src & 31);
+                const int64_t sp = base + pb * 32 + (src & 31);
                 const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
                 const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * c.cs_stride;
                 const int arg = exact_argmin_wave(c.X + sp * c.ldx, crun, c.cs_stride, c.k0 + srl, d, c.vec_x && c.vec_c);
@@ -565,7 +594,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         unsigned mv = 0;
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
+            const int64_t p = base + pb * 32 + n;
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 const int rl = S == 8 ? 0 : hl * ST + st;
@@ -584,79 +613,88 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         if (!FINAL) {
             // Exact sums: a point whose label changed moves its fixed-point row from the old cluster to the new
             // one.  Both lanes of the point's pair take part (each holds half of the features); one pair per pass.
-            const unsigned mvo = __shfl_xor(mv, 32, 64);
+            const unsigned mvo = xchg32(mv);
             unsigned both = hl ? (mvo | (mv << NBST)) : (mv | (mvo << NBST));
-            while (__ballot(both != 0u) != 0ull) {
-                const bool act = both != 0u;
-                const int bit = act ? __ffs(both) - 1 : 0;
-                both &= both - 1u;
-                const int oh = bit / NBST, idx = bit % NBST, pb = idx / ST, st = idx % ST;
-                int kk = 0;                         // the owner's (old << 8) | new
+            if (__ballot(both != 0u) != 0ull) {
+                // this lane's half of its points' rows on the fixed-point grid (zero beyond the last feature)
+                long long fx[NB][H];
 #pragma unroll
-                for (int i = 0; i < NBST; ++i)
-                    if (i == idx) kk = (m1[i / ST][i % ST] & 127) | (oldl[i / ST][i % ST] << 8);
-                const int kko = __shfl_xor(kk, 32, 64);
-                if (hl != oh) kk = kko;
-                const int nl = kk & 0xff, ol = kk >> 8;
-                const int r = S == 8 ? 0 : oh * ST + st;
-                const int rowbase = r * c.k0 + r * (r - 1) / 2;
-                if (act) {
-                    unsigned long long *so = c.sums + (rowbase + ol) * (DP + 1) + f0;
-                    unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+                for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
-                    for (int s = 0; s < H; ++s) {
-                        float xv = xraw[0][s];
+                    for (int s = 0; s < H; ++s) fx[pb][s] = s < nf ? to_fixed(xraw[pb][s], c.shift_s[f0 + s]) : 0ll;
+                do {
+                    const bool act = both != 0u;
+                    const int bit = act ? __ffs(both) - 1 : 0;
+                    both &= both - 1u;
+                    const int oh = bit / NBST, idx = bit % NBST, pb = idx / ST, st = idx % ST;
+                    int kk = 0;                         // the owner's (old << 8) | new
 #pragma unroll
-                        for (int q = 1; q < NB; ++q)
-                            if (pb == q) xv = xraw[q][s];
-                        if (s < nf) {
-                            const long long fx = to_fixed(xv, c.shift_s[f0 + s]);
-                            if (ol != 0xff) atomicAdd(so + s, (unsigned long long)(-fx));
-                            atomicAdd(sn + s, (unsigned long long)fx);
+                    for (int i = 0; i < NBST; ++i)
+                        if (i == idx) kk = (m1[i / ST][i % ST] & 127) | (oldl[i / ST][i % ST] << 8);
+                    const int kko = xchg32(kk);
+                    if (hl != oh) kk = kko;
+                    const int nl = kk & 0xff, ol = kk >> 8;
+                    const int r = S == 8 ? 0 : oh * ST + st;
+                    const int rowbase = r * c.k0 + r * (r - 1) / 2;
+                    if (act) {
+                        unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+                        long long v[H];
+#pragma unroll
+                        for (int s = 0; s < H; ++s) {
+                            v[s] = fx[0][s];
+#pragma unroll
+                            for (int q = 1; q < NB; ++q)
+                                if (pb == q) v[s] = fx[q][s];
+                            atomicAdd(sn + s, (unsigned long long)v[s]);
+                        }
+                        if (hl == 0) atomicAdd(&c.cnts[rowbase + nl], 1);
+                        if (ol != 0xff) {   // 0xff: no label yet, nothing to take back
+                            unsigned long long *so = c.sums + (rowbase + ol) * (DP + 1) + f0;
+#pragma unroll
+                            for (int s = 0; s < H; ++s) atomicAdd(so + s, (unsigned long long)(-v[s]));
+                            if (hl == 0) atomicAdd(&c.cnts[rowbase + ol], -1);
+                        }
+                        if (any_wide) {
+                            // rare: bits below the grid of a wide column go to a global integer accumulator
+                            const int64_t p = base + pb * 32 + n;
+                            const int64_t crow = c.grow0 + rowbase;
+                            for (int s = 0; s < nf; ++s) {
+                                if (c.wide_s[f0 + s] == 0) continue;
+                                const long long lo = fixed_low(c.X[p * c.ldx + f0 + s], c.shift_s[f0 + s]);
+                                if (lo == 0) continue;
+                                if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + f0 + s]), (unsigned long long)(-lo));
+                                atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + f0 + s]), (unsigned long long)lo);
+                            }
                         }
                     }
-                    if (hl == 0) {
-                        if (ol != 0xff) atomicAdd(&c.cnts[rowbase + ol], -1);
-                        atomicAdd(&c.cnts[rowbase + nl], 1);
-                    }
-                    if (any_wide) {
-                        // rare: bits below the grid of a wide column go to a global integer accumulator
-                        const int64_t p = p0 + wave * 32 * NB + pb * 32 + n;
-                        const int64_t crow = c.grow0 + rowbase;
-                        for (int s = 0; s < nf; ++s) {
-                            if (c.wide_s[f0 + s] == 0) continue;
-                            const long long lo = fixed_low(c.X[p * c.ldx + f0 + s], c.shift_s[f0 + s]);
-                            if (lo == 0) continue;
-                            if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + f0 + s]), (unsigned long long)(-lo));
-                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + f0 + s]), (unsigned long long)lo);
-                        }
-                    }
-                }
+                } while (__ballot(both != 0u) != 0ull);
             }
         }
         if (LOSS) {
             // loss of this assignment: each half-wave sums its features in fp64, the pair adds up
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb) {
-                const bool pvalid = p0 + wave * 32 * NB + pb * 32 + n < c.chunk_end;
+                const bool pvalid = base + pb * 32 + n < c.chunk_end;
                 for (int r = 0; r < c.n_runs; ++r) {
                     const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
                     int lab = 0;
 #pragma unroll
                     for (int st = 0; st < ST; ++st)
                         if (st == ost) lab = m1[pb][st] & 127;
-                    const int labo = __shfl_xor(lab, 32, 64);
+                    const int labo = xchg32(lab);
                     if (hl != oh) lab = labo;
                     double part = 0.0;
                     if (pvalid) {
                         const int lrow = r * c.k0 + r * (r - 1) / 2 + lab;
                         part = sqdist64_part(xraw[pb], c.cs + lrow * c.cs_stride + f0, nf);
                     }
-                    const double sum = __dadd_rn(part, __shfl_xor(part, 32, 64));
+                    const double sum = __dadd_rn(part, xchg32(part));
                     if (hl == 0) jloc[r] = __dadd_rn(jloc[r], sum);
                 }
             }
         }
+        cur = nxt;
+        nxt = nxt2;
     }
 }
 
@@ -667,8 +705,9 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
 
     const int b = blockIdx.y;
     if (a.status[b] != 0) return;
-    const int gi = blockIdx.x % plan.n_groups;
-    const int chunk = blockIdx.x / plan.n_groups;
+    // heaviest groups first: the dispatcher hands workgroups out in index order, light ones fill the end
+    const int gi = plan.sched[blockIdx.x / plan.n_chunks];
+    const int chunk = blockIdx.x % plan.n_chunks;
     const GroupDesc g = plan.g[gi];
     const int d = a.d;
     const int k0 = plan.k_min + g.run0;                                   // k of the group's first run
@@ -684,6 +723,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     int *shift_s = reinterpret_cast<int *>(smem + cv.misc + 128);         // [32]
     int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
     float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
+    int *next_slab = reinterpret_cast<int *>(smem + cv.misc + 448);
     double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][kWaves]
 
     const int tid = threadIdx.x;
@@ -704,6 +744,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
             const float *csrc = Cb + (int64_t)grow0 * d;
             for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[(e / d) * (d + 4) + e % d] = csrc[e];
         }
+        if (tid == 0) *next_slab = kWaves;
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
         if (!FINAL) {
             for (int e = tid; e < real_rows * (DP + 1); e += kThreads) sums[e] = 0ull;
@@ -716,6 +757,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     c.opA_s = opA_s;
     c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
     c.cs_stride = d + 4;
+    c.next_slab = next_slab;
     c.sums = sums; c.cnts = cnts; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
     c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
@@ -1216,6 +1258,14 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
         run += best_nr;
     }
     plan->total_tiles = tiles;
+    // launch order: groups by falling cost (tiles per point)
+    for (int i = 0; i < plan->n_groups; ++i) plan->sched[i] = (uint8_t)i;
+    for (int i = 1; i < plan->n_groups; ++i) {
+        const uint8_t v = plan->sched[i];
+        int j = i;
+        while (j > 0 && plan->g[plan->sched[j - 1]].n_tiles < plan->g[v].n_tiles) { plan->sched[j] = plan->sched[j - 1]; --j; }
+        plan->sched[j] = v;
+    }
     plan->total_rows = rows_before(k_min, plan->n_runs);
     // chunks: enough workgroups to fill the chip several times over; a chunk never exceeds 2^17 points
     const int tp = geo.tile_points;

@@ -51,6 +51,7 @@ struct SweepPlan {
     int32_t chunk_len;   // points per chunk (multiple of the tile size)
     int32_t dp;          // padded feature count: 8, 16 or 32
     GroupDesc g[kMaxGroups];
+    uint8_t sched[kMaxGroups];   // launch order: group indices by falling cost
 };
 
 // rows of runs k_min .. k_min+run-1
