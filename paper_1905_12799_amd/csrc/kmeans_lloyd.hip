@@ -1008,6 +1008,8 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
 {
     __shared__ float cs[RLS_MAX_K * DP];     // centred centroids of this run
     __shared__ float wmax[kThreads / 64];
+    __shared__ long long part_hi[INIT ? 1 : kThreads], part_cnt[INIT ? 1 : kThreads];
+    __shared__ unsigned long long part_lo[INIT ? 1 : kThreads];
     const int b = blockIdx.y, run = blockIdx.x, tid = threadIdx.x;
     if (a.status[b] != 0) return;
     const int d = a.d, k = plan.k_min + run;
@@ -1024,6 +1026,31 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
     // operand block of the group: per tile, tile_slots_of(DP) slots of 64 lanes x 8 bf16
     unsigned short *opA = reinterpret_cast<unsigned short *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
     constexpr int NK = ksteps_of(DP), NS = tile_slots_of(DP);
+
+    // A run with few (centroid, feature) elements splits the chunks over `nsl` thread slices per element, so that
+    // the per-chunk deltas are not read one after the other by a handful of threads; integer sums, any order.
+    const int E = k * DP;
+    const int nsl = (!INIT && E < kThreads) ? kThreads / E : 1;
+    if (nsl > 1) {
+        const int e = tid % E, sl = tid / E;
+        const int j = e / DP, l = e % DP;
+        long long hi = 0, cnt = 0;
+        unsigned long long lo = 0;
+        if (sl < nsl && l < d) {
+            const long long *psum = reinterpret_cast<const long long *>(wsb + a.off_psum) + (int64_t)(row0 + j) * d + l;
+            const int *pcnt = reinterpret_cast<const int *>(wsb + a.off_pcnt) + row0 + j;
+            const int c_begin = (int)((int64_t)plan.n_chunks * sl / nsl), c_end = (int)((int64_t)plan.n_chunks * (sl + 1) / nsl);
+            for (int c0 = c_begin; c0 < c_end; ++c0) {
+                const long long v = psum[(int64_t)c0 * plan.total_rows * d];
+                const unsigned long long nlo = lo + (unsigned long long)v;
+                hi += (v >> 63) + (nlo < lo ? 1 : 0);
+                lo = nlo;
+                cnt += pcnt[(int64_t)c0 * plan.total_rows];
+            }
+        }
+        part_hi[tid] = hi; part_lo[tid] = lo; part_cnt[tid] = cnt;
+        __syncthreads();
+    }
 
     for (int e = tid; e < k * DP; e += kThreads) {
         const int j = e / DP, l = e % DP;
@@ -1042,12 +1069,38 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
                 long long hi = tot[0];
                 unsigned long long lo = (unsigned long long)tot[1];
                 long long cnt = *totcnt;
-                for (int c0 = 0; c0 < plan.n_chunks; ++c0) {
-                    const long long v = psum[((int64_t)c0 * plan.total_rows + row0 + j) * d + l];
-                    const unsigned long long nlo = lo + (unsigned long long)v;
-                    hi += (v >> 63) + (nlo < lo ? 1 : 0);
-                    lo = nlo;
-                    cnt += pcnt[(int64_t)c0 * plan.total_rows + row0 + j];
+                if (nsl > 1) {
+                    for (int sl = 0; sl < nsl; ++sl) {
+                        const unsigned long long nlo = lo + part_lo[sl * E + e];
+                        hi += part_hi[sl * E + e] + (nlo < lo ? 1 : 0);
+                        lo = nlo;
+                        cnt += part_cnt[sl * E + e];
+                    }
+                } else {
+                    const long long *pe = psum + (int64_t)(row0 + j) * d + l;
+                    const int *pc = pcnt + row0 + j;
+                    const int64_t cstride = (int64_t)plan.total_rows * d;
+                    int c0 = 0;
+                    for (; c0 + 4 <= plan.n_chunks; c0 += 4) {   // four loads in flight
+                        long long v[4];
+                        int m[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) { v[u] = pe[(c0 + u) * cstride]; m[u] = pc[(int64_t)(c0 + u) * plan.total_rows]; }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const unsigned long long nlo = lo + (unsigned long long)v[u];
+                            hi += (v[u] >> 63) + (nlo < lo ? 1 : 0);
+                            lo = nlo;
+                            cnt += m[u];
+                        }
+                    }
+                    for (; c0 < plan.n_chunks; ++c0) {
+                        const long long v = pe[c0 * cstride];
+                        const unsigned long long nlo = lo + (unsigned long long)v;
+                        hi += (v >> 63) + (nlo < lo ? 1 : 0);
+                        lo = nlo;
+                        cnt += pc[(int64_t)c0 * plan.total_rows];
+                    }
                 }
                 tot[0] = hi;
                 tot[1] = (long long)lo;
