@@ -75,17 +75,12 @@ struct StepArgs {
     int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev;
 };
 
-// x * 2^shift truncated toward zero; exact whenever x is a multiple of 2^-shift
+// x * 2^shift truncated toward zero, |x * 2^shift| < 2^kGridBits; exact whenever x is a multiple of 2^-shift.
+// The scaling is exact in fp64; adding 2^52 + 2^51 leaves the integer in the low bits of the significand.
 __device__ inline long long to_fixed(float x, int shift)
 {
-    const unsigned u = __float_as_uint(x);
-    const int e0 = (int)((u >> 23) & 0xffu);
-    const unsigned m = (u & 0x7fffffu) | (e0 ? 0x800000u : 0u);      // subnormals: no hidden bit, exponent 1
-    const int sh = (e0 ? e0 : 1) - 150 + shift;
-    const long long up = (long long)m << min(max(sh, 0), 39);
-    const long long down = (long long)(m >> min(max(-sh, 0), 31));
-    const long long q = sh >= 0 ? up : down;
-    return (u >> 31) ? -q : q;
+    const double t = trunc(ldexp((double)x, shift));
+    return __double_as_longlong(__dadd_rn(t, 6755399441055744.0)) - 0x4338000000000000ll;
 }
 
 // The part of x below the column grid 2^-shift, scaled by 2^(shift + kLowBits): the bits that to_fixed drops.
@@ -168,20 +163,6 @@ __device__ inline void load_half_row(float (&dst)[H], const float *src, int nf, 
 #pragma unroll
         for (int l = 0; l < H; ++l) dst[l] = l < nf ? src[l] : 0.0f;
     }
-}
-
-// continues the fp64 direct-form sum `acc` over nf more features held in registers
-template <int H>
-__device__ inline double sqdist64_cont(double acc, const float (&x)[H], const float (&c)[H], int nf)
-{
-#pragma unroll
-    for (int l = 0; l < H; ++l) {
-        if (l < nf) {
-            const double diff = __dsub_rn((double)x[l], (double)c[l]);
-            acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-        }
-    }
-    return acc;
 }
 
 // The assignment as it is defined, by one whole wave: fp64 direct-form distances of one point to the k
@@ -421,19 +402,20 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         }
 
         // ---- distances tile by tile; the results of one block are folded while the matrix pipeline runs the next
-        bf16x8 a_cur[NS];
+        // (the tile loop is written out twice so that the operand buffers and accumulators alternate by name
+        // instead of being copied)
+        bf16x8 a_even[NS], a_odd[NS];
         auto load_a = [&](bf16x8 (&dst)[NS], int t) {
 #pragma unroll
             for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
         };
-        load_a(a_cur, 0);
+        load_a(a_even, 0);
         const float big = __int_as_float(kBigKey);
         floatx16 acc_prev = {big, big, big, big, big, big, big, big, big, big, big, big, big, big, big, big};
         int kidx_old[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e) kidx_old[e] = 0;
-        for (int t = 0; t < c.n_tiles; ++t) {
-            bf16x8 a_nxt[NS];
+        auto tile_step = [&](const bf16x8 (&a_cur)[NS], bf16x8 (&a_nxt)[NS], int t) {
             load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
             // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
             int kidx[16];
@@ -470,8 +452,14 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
-#pragma unroll
-            for (int sl = 0; sl < NS; ++sl) a_cur[sl] = a_nxt[sl];
+        };
+        {
+            int t = 0;
+            for (; t + 2 <= c.n_tiles; t += 2) {
+                tile_step(a_even, a_odd, t);
+                tile_step(a_odd, a_even, t + 1);
+            }
+            if (t < c.n_tiles) tile_step(a_even, a_odd, t);
         }
         fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
         // the next rows have arrived by now; asking for them here, before this step's stores are issued,
@@ -552,12 +540,28 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 float c1[H], c2[H];
                 load_half_row<H>(c1, crun + j1 * c.cs_stride, nf, c.vec_c);
                 load_half_row<H>(c2, crun + j2 * c.cs_stride, nf, c.vec_c);
+                // the squared differences do not depend on the running sum: both half-waves form theirs at once,
+                // then the lower half adds its own up, hands the sum over, and the upper half goes on with it
+                double t1[H], t2[H];
+#pragma unroll
+                for (int l = 0; l < H; ++l) {
+                    const double e1 = __dsub_rn((double)xs[l], (double)c1[l]), e2 = __dsub_rn((double)xs[l], (double)c2[l]);
+                    t1[l] = __dmul_rn(e1, e1);
+                    t2[l] = __dmul_rn(e2, e2);
+                }
                 double d1 = 0.0, d2 = 0.0;
-                if (hl == 0) { d1 = sqdist64_cont<H>(0.0, xs, c1, nf); d2 = sqdist64_cont<H>(0.0, xs, c2, nf); }
-                const double u1 = xchg32(d1), u2 = xchg32(d2);
+                if (hl == 0) {
+#pragma unroll
+                    for (int l = 0; l < H; ++l)
+                        if (l < nf) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
+                }
+                d1 = xchg32(d1);
+                d2 = xchg32(d2);
                 int win = j1;
                 if (hl == 1) {
-                    d1 = sqdist64_cont<H>(u1, xs, c1, nf); d2 = sqdist64_cont<H>(u2, xs, c2, nf);
+#pragma unroll
+                    for (int l = 0; l < H; ++l)
+                        if (l < nf) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
                     win = (d2 < d1 || (d2 == d1 && j2 < j1)) ? j2 : j1;
                 }
                 const int wino = xchg32(win);
