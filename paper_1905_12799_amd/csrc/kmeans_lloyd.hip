@@ -51,7 +51,7 @@ __host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_
     Carve c;
     int off = 0;
     c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (bf16 pieces + bias)
-    c.cs = off;      off += real_rows * (d + 4) * 4 / 16 * 16 + 16;        // centroids as given, row stride d + 4
+    c.cs = off;      off += real_rows * (dp + 4) * 4;                   // centroids as given, rows of dp + 4 floats, zero-padded
     c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point sum deltas
     c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
     c.misc = off;    off += 1024;
@@ -106,34 +106,6 @@ __device__ inline long long fixed_low(float x, int shift)
     return (u >> 31) ? -q : q;
 }
 
-__device__ inline double sqdist64(const float *x, const float *c, int d)
-{
-    double acc = 0.0;
-    for (int l = 0; l < d; ++l) {
-        const double diff = __dsub_rn((double)x[l], (double)c[l]);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-    }
-    return acc;
-}
-
-// same sum, rows read 16 bytes at a time (d a multiple of 4, both rows 16-byte aligned)
-__device__ inline double sqdist64_v4(const float *x, const float *c, int d)
-{
-    double acc = 0.0;
-    for (int l = 0; l < d; l += 4) {
-        const float4 xv = *reinterpret_cast<const float4 *>(x + l), cv = *reinterpret_cast<const float4 *>(c + l);
-        double diff = __dsub_rn((double)xv.x, (double)cv.x);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-        diff = __dsub_rn((double)xv.y, (double)cv.y);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-        diff = __dsub_rn((double)xv.z, (double)cv.z);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-        diff = __dsub_rn((double)xv.w, (double)cv.w);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-    }
-    return acc;
-}
-
 // value of the lane 32 places away (the other half-wave), by a register swap: no trip through LDS
 __device__ inline int xchg32(int v)
 {
@@ -148,33 +120,54 @@ __device__ inline double xchg32(double v)
     return __hiloint2double(hi, lo);
 }
 
-// half of a centroid row (the features of one half-wave) from LDS into registers
+// half of a centroid row (the features of one half-wave) from the zero-padded LDS copy into registers
 template <int H>
-__device__ inline void load_half_row(float (&dst)[H], const float *src, int nf, bool vec)
+__device__ inline void load_half_row(float (&dst)[H], const float *src)
 {
-    if (vec) {
 #pragma unroll
-        for (int l = 0; l < H; l += 4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (l < nf) v = *reinterpret_cast<const float4 *>(src + l);
-            dst[l] = v.x; dst[l + 1] = v.y; dst[l + 2] = v.z; dst[l + 3] = v.w;
-        }
-    } else {
-#pragma unroll
-        for (int l = 0; l < H; ++l) dst[l] = l < nf ? src[l] : 0.0f;
+    for (int l = 0; l < H; l += 4) {
+        const float4 v = *reinterpret_cast<const float4 *>(src + l);
+        dst[l] = v.x; dst[l + 1] = v.y; dst[l + 2] = v.z; dst[l + 3] = v.w;
     }
 }
 
-// The assignment as it is defined, by one whole wave: fp64 direct-form distances of one point to the k
-// centroids of a run (one or two per lane), then the lexicographic minimum of (distance, index) over the wave.
-// Every lane returns the winner.
-__device__ inline int exact_argmin_wave(const float *xrow, const float *crun, int cstride, int k, int d, bool vec)
+// The assignment as it is defined, by one whole wave: fp64 direct-form distances sum_l (x_l - c_l)^2, features in
+// rising order, of one point to the k centroids of a run (one or two per lane), then the lexicographic minimum of
+// (distance, index) over the wave.  Every lane returns the winner.  The centroid rows come from the LDS copy,
+// which is zero beyond the last feature, as is the register copy of the point: padded terms add +0.
+template <int DP>
+__device__ inline int exact_argmin_wave(const float *xrow, const float *crun, int cstride, int k, int d, bool vec_x)
 {
     const int lane = threadIdx.x & 63;
+    float x[DP];
+    if (vec_x) {
+#pragma unroll
+        for (int l = 0; l < DP; l += 4) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (l < d) v = *reinterpret_cast<const float4 *>(xrow + l);
+            x[l] = v.x; x[l + 1] = v.y; x[l + 2] = v.z; x[l + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int l = 0; l < DP; ++l) x[l] = l < d ? xrow[l] : 0.0f;
+    }
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int j = lane; j < k; j += 64) {
-        const double dist = vec ? sqdist64_v4(xrow, crun + j * cstride, d) : sqdist64(xrow, crun + j * cstride, d);
+        const float *crow = crun + j * cstride;
+        double dist = 0.0;
+#pragma unroll
+        for (int l = 0; l < DP; l += 4) {
+            const float4 cv = *reinterpret_cast<const float4 *>(crow + l);
+            double diff = __dsub_rn((double)x[l], (double)cv.x);
+            dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+            diff = __dsub_rn((double)x[l + 1], (double)cv.y);
+            dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+            diff = __dsub_rn((double)x[l + 2], (double)cv.z);
+            dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+            diff = __dsub_rn((double)x[l + 3], (double)cv.w);
+            dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+        }
         if (dist < best) { best = dist; arg = j; }
     }
 #pragma unroll
@@ -252,8 +245,7 @@ __device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int
 // (matrix pipeline / vector ALU / LDS atomics) overlap on a SIMD.
 struct WaveCtx {
     const uint4 *opA_s;           // LDS: operand slots of the group's tiles
-    const float *cs;              // the group's centroids as given (LDS copy or global), row stride cs_stride
-    int cs_stride;
+    const float *cs;              // LDS: the group's centroids as given, rows of DP + 4 floats, zero past feature d
     unsigned long long *sums;     // LDS: fixed-point sum deltas [row][DP + 1]
     int *cnts;                    // LDS: member count deltas [row]
     const float *mu_s;            // LDS: column means [32]
@@ -268,7 +260,7 @@ struct WaveCtx {
     long long *losum;             // global: low-order sums of wide columns [row][d]
     int64_t chunk_begin, chunk_end;
     int *next_slab;               // LDS: next slab of the chunk to hand out
-    bool vec_x, vec_c;   // vec_x / vec_c: rows of X / of the centroid copy may be read 16 bytes at a time
+    bool vec_x;                   // rows of X may be read 16 bytes at a time
     float eps_a;
 };
 
@@ -289,6 +281,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     constexpr int TP = tile_points_of(DP);          // points per workgroup step
     constexpr int NB = TP / (32 * kWaves);          // blocks of 32 points per wave and step
     constexpr int H = DP / 2;                       // features per half-wave
+    constexpr int CS = DP + 4;                      // row stride of the LDS copy of the centroids
     constexpr int NK = ksteps_of(DP);               // K-steps of 16 per cross term
     constexpr int NS = tile_slots_of(DP);           // operand slots per tile and lane
     constexpr int HP = 8 * NK;                      // feature slots per half-wave (H padded to whole K-steps)
@@ -528,7 +521,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 if (hl != oh) kk = kko;
                 const int j1 = kk & 0xff, j2 = kk >> 8;
                 const int rl = S == 8 ? 0 : oh * ST + st;
-                const float *crun = c.cs + (rl * c.k0 + rl * (rl - 1) / 2) * c.cs_stride + f0;
+                const float *crun = c.cs + (rl * c.k0 + rl * (rl - 1) / 2) * CS + f0;
                 float xs[H];
 #pragma unroll
                 for (int s = 0; s < H; ++s) {
@@ -538,8 +531,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                         if (pb == q) xs[s] = xraw[q][s];
                 }
                 float c1[H], c2[H];
-                load_half_row<H>(c1, crun + j1 * c.cs_stride, nf, c.vec_c);
-                load_half_row<H>(c2, crun + j2 * c.cs_stride, nf, c.vec_c);
+                load_half_row<H>(c1, crun + j1 * CS);
+                load_half_row<H>(c2, crun + j2 * CS);
                 // the squared differences do not depend on the running sum: both half-waves form theirs at once,
                 // then the lower half adds its own up, hands the sum over, and the upper half goes on with it
                 double t1[H], t2[H];
@@ -550,18 +543,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     t2[l] = __dmul_rn(e2, e2);
                 }
                 double d1 = 0.0, d2 = 0.0;
+                // (terms past the last feature are +0 and leave a sum as it is)
                 if (hl == 0) {
 #pragma unroll
-                    for (int l = 0; l < H; ++l)
-                        if (l < nf) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
+                    for (int l = 0; l < H; ++l) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
                 }
                 d1 = xchg32(d1);
                 d2 = xchg32(d2);
                 int win = j1;
                 if (hl == 1) {
 #pragma unroll
-                    for (int l = 0; l < H; ++l)
-                        if (l < nf) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
+                    for (int l = 0; l < H; ++l) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
                     win = (d2 < d1 || (d2 == d1 && j2 < j1)) ? j2 : j1;
                 }
                 const int wino = xchg32(win);
@@ -582,8 +574,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
                 const int64_t sp = base + pb * 32 + (src & 31);
                 const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
-                const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * c.cs_stride;
-                const int arg = exact_argmin_wave(c.X + sp * c.ldx, crun, c.cs_stride, c.k0 + srl, d, c.vec_x && c.vec_c);
+                const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * CS;
+                const int arg = exact_argmin_wave<DP>(c.X + sp * c.ldx, crun, CS, c.k0 + srl, d, c.vec_x);
                 if (lane == src) {
                     pend3 &= pend3 - 1u;
 #pragma unroll
@@ -625,7 +617,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
-                    for (int s = 0; s < H; ++s) fx[pb][s] = s < nf ? to_fixed(xraw[pb][s], c.shift_s[f0 + s]) : 0ll;
+                    for (int s = 0; s < H; ++s) fx[pb][s] = to_fixed(xraw[pb][s], c.shift_s[f0 + s]);   // xraw is 0 past the last feature
                 do {
                     const bool act = both != 0u;
                     const int bit = act ? __ffs(both) - 1 : 0;
@@ -690,7 +682,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     double part = 0.0;
                     if (pvalid) {
                         const int lrow = r * c.k0 + r * (r - 1) / 2 + lab;
-                        part = sqdist64_part(xraw[pb], c.cs + lrow * c.cs_stride + f0, nf);
+                        part = sqdist64_part(xraw[pb], c.cs + lrow * CS + f0, nf);
                     }
                     const double sum = __dadd_rn(part, xchg32(part));
                     if (hl == 0) jloc[r] = __dadd_rn(jloc[r], sum);
@@ -746,7 +738,10 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
         {
             const float *csrc = Cb + (int64_t)grow0 * d;
-            for (int e = tid; e < real_rows * d; e += kThreads) cs_lds[(e / d) * (d + 4) + e % d] = csrc[e];
+            for (int e = tid; e < real_rows * DP; e += kThreads) {
+                const int j = e / DP, l = e % DP;
+                cs_lds[j * (DP + 4) + l] = l < d ? csrc[j * d + l] : 0.0f;
+            }
         }
         if (tid == 0) *next_slab = kWaves;
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
@@ -760,7 +755,6 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     WaveCtx c;
     c.opA_s = opA_s;
     c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
-    c.cs_stride = d + 4;
     c.next_slab = next_slab;
     c.sums = sums; c.cnts = cnts; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
@@ -771,7 +765,6 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     c.chunk_end = min(a.N, c.chunk_begin + plan.chunk_len);
     // 16-byte loads need whole quads of features and aligned rows
     c.vec_x = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
-    c.vec_c = d % 4 == 0;
     // bound on the error of the matrix-pipeline distances relative to |x'|^2 + |c'|^2: dropped piece products
     // (2^-23), seven chained fp32 accumulations of up to 16 products each, rounding of the norms and of the centring
     c.eps_a = (float)(8 * (DP + 8)) * 1.1920928955078125e-07f;   // 8 (DP + 8) 2^-23
