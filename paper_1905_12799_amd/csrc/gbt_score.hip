@@ -54,15 +54,30 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
         }
         for (int e = tid; e < tc * n_leaf; e += P) leaves[e] = f.leaf[(size_t)t0 * n_leaf + e];
         __syncthreads();
-        for (int t = 0; t < tc; ++t) {
-            const uint2 *tn = nodes + (size_t)t * n_int;
-            int n = 0;
-            for (int lev = 0; lev < f.depth; ++lev) {
-                const uint2 nd = tn[n];
-                const float xv = xs[nd.x * P + tid];
-                n = 2 * n + 1 + ((xv < __uint_as_float(nd.y)) ? 0 : 1);
+        // Four trees are walked side by side: a walk is a chain of dependent LDS reads (node, then feature value),
+        // and independent chains keep more of them in flight.  The leaves are still added in tree order.
+        constexpr int W = 4;
+        for (int t = 0; t < tc; t += W) {
+            const uint2 *tn[W];
+            int n[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                tn[w] = nodes + (size_t)min(t + w, tc - 1) * n_int;
+                n[w] = 0;
             }
-            sum = sum + leaves[t * n_leaf + (n - n_int)];
+            for (int lev = 0; lev < f.depth; ++lev) {
+                uint2 nd[W];
+#pragma unroll
+                for (int w = 0; w < W; ++w) nd[w] = tn[w][n[w]];
+                float xv[W];
+#pragma unroll
+                for (int w = 0; w < W; ++w) xv[w] = xs[nd[w].x * P + tid];
+#pragma unroll
+                for (int w = 0; w < W; ++w) n[w] = 2 * n[w] + 1 + ((xv[w] < __uint_as_float(nd[w].y)) ? 0 : 1);
+            }
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+                if (t + w < tc) sum = sum + leaves[(t + w) * n_leaf + (n[w] - n_int)];
         }
     }
     if (valid) score[row] = sum;

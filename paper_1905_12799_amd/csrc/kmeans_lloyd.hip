@@ -1270,7 +1270,7 @@ int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows)
     return carve_lds(dp, d, n_tiles, real_rows).total;
 }
 
-int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, SweepPlan *plan)
+int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch, SweepPlan *plan)
 {
     const int dp = padded_d(d);
     const LloydGeometry geo = lloyd_geometry(dp);
@@ -1317,10 +1317,12 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, Swee
         plan->sched[j] = v;
     }
     plan->total_rows = rows_before(k_min, plan->n_runs);
-    // chunks: enough workgroups to fill the chip several times over; a chunk never exceeds 2^17 points
+    // chunks: enough workgroups over the whole batch to fill the chip several times over (a workgroup stages its
+    // group's rows once, so more and shorter chunks only add set-up); a chunk never exceeds 2^17 points
     const int tp = geo.tile_points;
     const int64_t tiles_total = (N + tp - 1) / tp;
-    int64_t want = (1024 + plan->n_groups - 1) / plan->n_groups;
+    const int64_t units = (int64_t)plan->n_groups * (batch > 0 ? batch : 1);
+    int64_t want = (1024 + units - 1) / units;
     if (want > tiles_total) want = tiles_total;
     if (want < 1) want = 1;
     int64_t chunk_len = ((tiles_total + want - 1) / want) * tp;

@@ -132,7 +132,7 @@ int64_t rls_kmeans_sweep_workspace_bytes(int64_t N, int32_t d, int32_t k_min, in
     const int32_t rc = check_sweep(N, d, k_min, k_max, batch);
     if (rc != RLS_OK) return rc;
     SweepPlan plan;
-    const int32_t prc = make_sweep_plan(N, d, k_min, k_max, &plan);
+    const int32_t prc = make_sweep_plan(N, d, k_min, k_max, batch, &plan);
     if (prc != RLS_OK) return prc;
     SweepLayout L;
     sweep_layout(plan, N, d, k_max, batch, &L);
@@ -148,7 +148,7 @@ int32_t rls_kmeanspp_chain(const float *X_dev, int64_t N, int32_t d, int64_t ldx
     rc = check_sweep(N, d, k_max, k_max, 1);
     if (rc != RLS_OK) return rc;
     SweepPlan plan;
-    rc = make_sweep_plan(N, d, k_max, k_max, &plan);
+    rc = make_sweep_plan(N, d, k_max, k_max, 1, &plan);
     if (rc != RLS_OK) return rc;
     SweepLayout L;
     sweep_layout(plan, N, d, k_max, 1, &L);
@@ -175,7 +175,7 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
     if (iters < 0) return RLS_ERR_INVALID_ARG;
     if (batch > 1 && x_batch_stride < N * ldx - (ldx - d)) return RLS_ERR_SHAPE;
     SweepPlan plan;
-    rc = make_sweep_plan(N, d, k_min, k_max, &plan);
+    rc = make_sweep_plan(N, d, k_min, k_max, batch, &plan);
     if (rc != RLS_OK) return rc;
     SweepLayout L;
     sweep_layout(plan, N, d, k_max, batch, &L);
