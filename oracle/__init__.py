@@ -154,6 +154,35 @@ def snap_to_valid(centroids, offsets, values) -> np.ndarray:
     return cfg
 
 
+def knob_modes(X, offsets, values) -> Tuple[np.ndarray, np.ndarray]:
+    """mode(s_Theta): per knob the domain index most points take; also the counts of every domain entry."""
+    X = _f32(X)
+    N, d = X.shape
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    values = _f32(values)
+    n_knobs = offsets.shape[0] - 1
+    mode = np.empty(n_knobs, dtype=np.int32)
+    hist = np.empty(int(offsets[-1]), dtype=np.int64)
+    rc = lib().orc_knob_modes(_p(X), ctypes.c_int64(N), ctypes.c_int32(d), ctypes.c_int64(d), ctypes.c_int32(n_knobs),
+                              _p(offsets), _p(values), _p(mode), _p(hist))
+    _check(rc, "knob_modes")
+    return mode, hist
+
+
+def replace_visited(cfg, visited, mode_cfg) -> Tuple[np.ndarray, np.ndarray]:
+    """Rows of cfg found among the visited rows become mode_cfg; returns (new cfg, replaced flags)."""
+    cfg = np.array(cfg, dtype=np.int32, order="C", copy=True)
+    k, n_knobs = cfg.shape
+    visited = np.ascontiguousarray(visited, dtype=np.int32).reshape(-1, n_knobs)
+    mode_cfg = np.ascontiguousarray(mode_cfg, dtype=np.int32)
+    replaced = np.zeros(k, dtype=np.int32)
+    rc = lib().orc_replace_visited(_p(cfg), ctypes.c_int32(k), ctypes.c_int32(n_knobs),
+                                   _p(visited) if visited.shape[0] else None, ctypes.c_int64(visited.shape[0]),
+                                   _p(mode_cfg), _p(replaced))
+    _check(rc, "replace_visited")
+    return cfg, replaced
+
+
 def two_nearest(x, C) -> Tuple[float, float, int]:
     x = _f32(x)
     C = _f32(C)

@@ -322,6 +322,66 @@ int32_t orc_snap_to_valid(const float *centroids, int32_t k, int32_t d, int64_t 
     return ORC_OK;
 }
 
+/* ------------------------------------------------------------------------ */
+/* mode(s_Theta) of Algorithm 1, read as Sec. 4.2 states it: the             */
+/* configuration made of the mode of each dimension.  A point's value in      */
+/* knob j is the domain entry nearest to its coordinate j (as in the snap    */
+/* above); the mode is the entry most points take, the lowest index among    */
+/* equally frequent ones.  hist (optional) receives the counts of all        */
+/* entries, laid out like values.                                             */
+int32_t orc_knob_modes(const float *X, int64_t N, int32_t d, int64_t ldx, int32_t n_knobs, const int32_t *offsets,
+                       const float *values, int32_t *mode_cfg, int64_t *hist)
+{
+    if (!X || !offsets || !values || !mode_cfg || N < 1 || n_knobs < 1 || n_knobs > d || ldx < d) return ORC_ERR_ARG;
+    for (int32_t j = 0; j < n_knobs; ++j)
+        if (offsets[j + 1] <= offsets[j]) return ORC_ERR_ARG;
+    int64_t *count = (int64_t *)calloc((size_t)offsets[n_knobs], sizeof(int64_t));
+    if (!count) return ORC_ERR_ARG;
+    for (int64_t i = 0; i < N; ++i) {
+        for (int32_t j = 0; j < n_knobs; ++j) {
+            const double x = (double)X[i * ldx + j];
+            double best = INFINITY;
+            int32_t arg = offsets[j];
+            for (int32_t v = offsets[j]; v < offsets[j + 1]; ++v) {
+                const double gap = fabs(x - (double)values[v]);
+                if (gap < best) { best = gap; arg = v; }
+            }
+            count[arg] += 1;
+        }
+    }
+    for (int32_t j = 0; j < n_knobs; ++j) {
+        int32_t arg = offsets[j];
+        for (int32_t v = offsets[j] + 1; v < offsets[j + 1]; ++v)
+            if (count[v] > count[arg]) arg = v;
+        mode_cfg[j] = arg - offsets[j];
+    }
+    if (hist) memcpy(hist, count, (size_t)offsets[n_knobs] * sizeof(int64_t));
+    free(count);
+    return ORC_OK;
+}
+
+/* The last loop of Algorithm 1: a sample that is already among the visited  */
+/* configurations v_Theta is replaced by mode(s_Theta).  Configurations are  */
+/* rows of n_knobs domain indices; replaced[i] tells which rows changed.      */
+int32_t orc_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, const int32_t *visited, int64_t n_visited,
+                            const int32_t *mode_cfg, int32_t *replaced)
+{
+    if (!cfg || !mode_cfg || !replaced || k < 1 || n_knobs < 1 || n_visited < 0 || (n_visited > 0 && !visited)) return ORC_ERR_ARG;
+    for (int32_t i = 0; i < k; ++i) {
+        int32_t found = 0;
+        for (int64_t v = 0; v < n_visited && !found; ++v) {
+            int32_t same = 1;
+            for (int32_t j = 0; j < n_knobs; ++j)
+                if (visited[v * n_knobs + j] != cfg[i * n_knobs + j]) { same = 0; break; }
+            found = same;
+        }
+        replaced[i] = found;
+        if (found)
+            for (int32_t j = 0; j < n_knobs; ++j) cfg[i * n_knobs + j] = mode_cfg[j];
+    }
+    return ORC_OK;
+}
+
 /* threads the annotated assignment loop runs on */
 int32_t orc_threads(void)
 {
