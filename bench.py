@@ -3,8 +3,9 @@
 
 One step = one pass of the whole path over one synthetic trajectory already resident in HBM:
 tree-ensemble scoring of every configuration, the k-means++ chain, the Lloyd sweep over all k
-(assign + update rounds and the final assignment with labels and inertia), the knee pick on the host
-and the snap of the chosen centroids.  The headline value is config-iterations per second:
+(assign + update rounds and the final assignment with labels and inertia), the knee pick on the host,
+the snap of the chosen centroids, the per-dimension mode of the trajectory and the replacement of samples
+that were visited before.  The headline value is config-iterations per second:
 N x (number of k) x (Lloyd rounds) per step divided by the step time.
 
 Prints ONE JSON line.  `roofline` describes the dominant kernel (the fused assign + update Lloyd step),
@@ -63,6 +64,8 @@ def main() -> int:
     X = torch.as_tensor(X_host).cuda()
     forests = [rls.DeviceForest.from_host(p.forest) for p in probs]
     domains = [rls.DeviceDomains(p.dom_offsets, p.dom_values) for p in probs]
+    n_visited = 65536
+    visited = [torch.as_tensor(synth.visited_configs(p, n_visited, w.seed + 1000 + b)).cuda() for b, p in enumerate(probs)]
     B = w.batch
     n_k = w.k_max - w.k_min + 1
     ws_bytes = rls.kmeans_sweep_workspace_bytes(w.N, w.d, w.k_min, w.k_max, B)
@@ -70,10 +73,11 @@ def main() -> int:
     scores = torch.empty((B, w.N) if batched else (w.N,), dtype=torch.float32, device="cuda")
     seeds = [w.seed + b for b in range(B)]
     knee_const = 1.05
+    hists = [torch.empty(dm.n_values, dtype=torch.int32, device="cuda") for dm in domains]
     want_labels = not args.no_labels
 
     ev = {name: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for name in ("score", "sweep", "snap")}
+          for name in ("score", "sweep", "snap", "modes_visited")}
     stage_ms = {name: 0.0 for name in ev}
 
     def step(record: bool):
@@ -96,18 +100,23 @@ def main() -> int:
         if bool((status != 0).any()):
             raise RuntimeError(f"sweep status {status.tolist()}")
         ev["snap"][0].record()
-        chosen = []
+        chosen, cfgs = [], []
         if batched:
             # one k per space; snap each space's chosen centroids (same k needed for a batched call, so loop)
             for b in range(B):
                 k = rls.pick_knee(inertia[b].tolist(), w.k_min, w.k_max, knee_const)
                 chosen.append(k)
-                rls.snap_to_valid(res.centroids_of(k, b), domains[b])
+                cfgs.append(rls.snap_to_valid(res.centroids_of(k, b), domains[b]))
         else:
             k = rls.pick_knee(inertia.tolist(), w.k_min, w.k_max, knee_const)
             chosen.append(k)
-            rls.snap_to_valid(res.centroids_of(k), domains[0])
+            cfgs.append(rls.snap_to_valid(res.centroids_of(k), domains[0]))
         ev["snap"][1].record()
+        ev["modes_visited"][0].record()
+        for b in range(B):
+            mode, _ = rls.knob_modes(X[b] if batched else X, domains[b], hist=hists[b])
+            rls.replace_visited(cfgs[b], visited[b], mode)
+        ev["modes_visited"][1].record()
         if record:
             torch.cuda.synchronize()
             for name in ev:
@@ -166,7 +175,8 @@ def main() -> int:
                    "knee_const": knee_const, "chosen_k": chosen[:4]},
         "configs_scored_per_s": float(w.N) * B / (score_ms * 1e-3),
         "sweep_config_iter_per_s": point_iters / (sweep_ms * 1e-3),
-        "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / args.steps},
+        "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / args.steps,
+                     "modes_visited": stage_ms["modes_visited"] / args.steps},
         "roofline": roofline,
     }
 

@@ -9,6 +9,8 @@
  *   rls_kmeans_sweep    k-means(s_Theta, k) for every k of a range: centroids, clusters, loss
  *   rls_pick_knee       the knee test on the loss curve (host, scalar)
  *   rls_snap_to_valid   NextSamples = Centroids, as valid configurations
+ *   rls_knob_modes      mode(s_Theta), dimension by dimension
+ *   rls_replace_visited samples already in v_Theta give way to mode(s_Theta)
  *
  * Conventions
  *   - Plain C. Every call returns an int32_t status: RLS_OK or a negative RLS_ERR_* code.
@@ -176,6 +178,34 @@ int32_t rls_snap_to_valid(const float *centroids_dev, int32_t k, int32_t d, int6
 int32_t rls_snap_to_valid_batched(int32_t batch, const float *centroids_dev, int32_t k, int32_t d, int64_t ldc,
                                   int64_t c_batch_stride, const rls_knob_domains *domains, int32_t *cfg_dev,
                                   void *stream);
+
+/*
+ * mode(s_Theta) of Algorithm 1, which Sec. 4.2 describes as the configuration "generated from modes of each
+ * dimension": for every knob j, the domain index that most rows of the trajectory take, a row's value in
+ * knob j being the domain entry nearest to its coordinate j (same rule as rls_snap_to_valid: |x - v| in
+ * fp64, ties to the lower index).  Equally frequent entries: the lower index.
+ *   X_dev        [N][ldx] fp32, N <= 2^26
+ *   mode_cfg_dev [n_knobs] int32 (written)
+ *   hist_dev     [offsets[n_knobs]] int32 counts of every domain entry, laid out like values_dev; used as
+ *                scratch and left holding the counts.  At most RLS_MAX_DOMAIN_VALUES entries in total.
+ * domains->offsets_dev and values_dev are device arrays; n_total_values = offsets[n_knobs] is passed by the
+ * caller (the library does not read device memory on the host).
+ */
+#define RLS_MAX_DOMAIN_VALUES 8192
+int32_t rls_knob_modes(const float *X_dev, int64_t N, int32_t d, int64_t ldx, const rls_knob_domains *domains,
+                       int32_t n_total_values, int32_t *mode_cfg_dev, int32_t *hist_dev, void *stream);
+
+/*
+ * The last loop of Algorithm 1: a sample that is already among the visited configurations v_Theta is
+ * replaced by mode(s_Theta).  Configurations are rows of n_knobs domain indices.
+ *   cfg_dev      [k][n_knobs] int32, updated in place
+ *   visited_dev  [n_visited][n_knobs] int32 (may be null when n_visited == 0)
+ *   mode_cfg_dev [n_knobs] int32
+ *   replaced_dev [k] int32 (written): 1 where the row was replaced
+ * The replacement is not checked against v_Theta again (the paper's loop does not).
+ */
+int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const int32_t *visited_dev,
+                            int64_t n_visited, const int32_t *mode_cfg_dev, int32_t *replaced_dev, void *stream);
 
 /*
  * Timing aid for benchmarks (not part of the paper's method).  While enabled, rls_kmeans_sweep[_batched]

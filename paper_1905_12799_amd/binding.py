@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Sequence
+from typing import Optional, Sequence, Tuple
 
 import torch
 
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.rls_snap_to_valid.argtypes = [vp, i32, i32, i64, ctypes.POINTER(_Domains), vp, vp]
         L.rls_snap_to_valid_batched.restype = i32
         L.rls_snap_to_valid_batched.argtypes = [i32, vp, i32, i32, i64, i64, ctypes.POINTER(_Domains), vp, vp]
+        L.rls_knob_modes.restype = i32
+        L.rls_knob_modes.argtypes = [vp, i64, i32, i64, ctypes.POINTER(_Domains), i32, vp, vp, vp]
+        L.rls_replace_visited.restype = i32
+        L.rls_replace_visited.argtypes = [vp, i32, i32, vp, i64, vp, vp, vp]
         L.rls_profile_enable.restype = i32
         L.rls_profile_enable.argtypes = [i32]
         L.rls_profile_read.restype = i32
@@ -149,6 +153,7 @@ class DeviceDomains:
         self.offsets = torch.as_tensor(offsets, dtype=torch.int32).contiguous().to(device)
         self.values = torch.as_tensor(values, dtype=torch.float32).contiguous().to(device)
         self.n_knobs = int(self.offsets.numel()) - 1
+        self.n_values = int(self.values.numel())
 
     def struct(self) -> _Domains:
         return _Domains(self.n_knobs, self.offsets.data_ptr(), self.values.data_ptr())
@@ -293,6 +298,36 @@ def snap_to_valid(centroids: torch.Tensor, domains: DeviceDomains, out: Optional
     _check(lib().rls_snap_to_valid(_ptr(centroids), k, d, centroids.stride(0), ctypes.byref(st), _ptr(out), _stream()),
            "rls_snap_to_valid")
     return out
+
+
+def knob_modes(X: torch.Tensor, domains: DeviceDomains, hist: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """mode(s_Theta): per knob the domain index most rows take; returns (mode_cfg [n_knobs], hist [n_values])."""
+    _mat(X, "X")
+    N, d = X.shape
+    mode = torch.empty(domains.n_knobs, dtype=torch.int32, device=X.device)
+    hist = torch.empty(domains.n_values, dtype=torch.int32, device=X.device) if hist is None else _dev(hist, torch.int32, "hist")
+    st = domains.struct()
+    _check(lib().rls_knob_modes(_ptr(X), N, d, X.stride(0), ctypes.byref(st), domains.n_values, _ptr(mode), _ptr(hist),
+                                _stream()), "rls_knob_modes")
+    return mode, hist
+
+
+def replace_visited(cfg: torch.Tensor, visited: Optional[torch.Tensor], mode_cfg: torch.Tensor) -> torch.Tensor:
+    """Rows of cfg (int32 [k][n_knobs], updated in place) found among the visited rows become mode_cfg; returns flags [k]."""
+    _dev(cfg, torch.int32, "cfg")
+    k, n_knobs = cfg.shape
+    if not cfg.is_contiguous():
+        raise ValueError("cfg must be contiguous")
+    n_visited = 0 if visited is None else int(visited.shape[0])
+    if n_visited:
+        _dev(visited, torch.int32, "visited")
+        if not visited.is_contiguous() or visited.shape[1] != n_knobs:
+            raise ValueError("visited must be contiguous [V][n_knobs]")
+    replaced = torch.empty(k, dtype=torch.int32, device=cfg.device)
+    _check(lib().rls_replace_visited(_ptr(cfg), k, n_knobs, _ptr(visited) if n_visited else None, n_visited,
+                                     _ptr(_dev(mode_cfg, torch.int32, "mode_cfg")), _ptr(replaced), _stream()),
+           "rls_replace_visited")
+    return replaced
 
 
 def snap_to_valid_batched(centroids: torch.Tensor, domains: Sequence[DeviceDomains],

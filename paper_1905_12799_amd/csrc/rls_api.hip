@@ -250,4 +250,29 @@ int32_t rls_snap_to_valid(const float *centroids_dev, int32_t k, int32_t d, int6
     return rls_snap_to_valid_batched(1, centroids_dev, k, d, ldc, 0, domains, cfg_dev, stream);
 }
 
+int32_t rls_knob_modes(const float *X_dev, int64_t N, int32_t d, int64_t ldx, const rls_knob_domains *domains,
+                       int32_t n_total_values, int32_t *mode_cfg_dev, int32_t *hist_dev, void *stream)
+{
+    const int32_t rc = check_matrix(X_dev, N, d, ldx);
+    if (rc != RLS_OK) return rc;
+    if (!domains || !mode_cfg_dev || !hist_dev) return RLS_ERR_NULL;
+    if (!domains->offsets_dev || !domains->values_dev) return RLS_ERR_NULL;
+    if (domains->n_knobs < 1 || domains->n_knobs > d) return RLS_ERR_SHAPE;
+    if (n_total_values < domains->n_knobs || n_total_values > RLS_MAX_DOMAIN_VALUES) return RLS_ERR_INVALID_ARG;
+    const DomainArgs dm{domains->n_knobs, domains->offsets_dev, domains->values_dev};
+    RLS_HIP_TRY(launch_knob_modes(X_dev, N, ldx, dm, n_total_values, mode_cfg_dev, hist_dev, (hipStream_t)stream));
+    return RLS_OK;
+}
+
+int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const int32_t *visited_dev,
+                            int64_t n_visited, const int32_t *mode_cfg_dev, int32_t *replaced_dev, void *stream)
+{
+    if (!cfg_dev || !mode_cfg_dev || !replaced_dev) return RLS_ERR_NULL;
+    if (k < 1 || n_knobs < 1 || n_knobs > RLS_MAX_D || n_visited < 0) return RLS_ERR_INVALID_ARG;
+    if (n_visited > 0 && !visited_dev) return RLS_ERR_NULL;
+    RLS_HIP_TRY(launch_replace_visited(cfg_dev, k, n_knobs, visited_dev, n_visited, mode_cfg_dev, replaced_dev,
+                                       (hipStream_t)stream));
+    return RLS_OK;
+}
+
 }  // extern "C"

@@ -238,6 +238,19 @@ def make_problem(w: Workload, conv: Sequence[int] | None = None, seed: int | Non
     return Problem(X, forest, offs, vals, space, comp)
 
 
+def visited_configs(p: Problem, n_visited: int, seed: int) -> np.ndarray:
+    """Stand-in for the history v_Theta: int32 [n_visited][n_knobs] domain indices, half of them rows of the
+    trajectory itself (configurations the search has been at), half uniform draws from the space."""
+    rng = np.random.default_rng(seed)
+    n_knobs = p.space.n_knobs
+    n_traj = min(n_visited // 2, p.X.shape[0])
+    rows = rng.choice(p.X.shape[0], size=n_traj, replace=False)
+    sizes = np.diff(p.dom_offsets)
+    traj = np.clip(np.rint(p.X[rows, :n_knobs]).astype(np.int64), 0, sizes[None, :] - 1)
+    rest = sample_knobs_uniform(p.space, n_visited - n_traj, rng)
+    return np.ascontiguousarray(np.concatenate([traj, rest], axis=0), dtype=np.int32)
+
+
 def make_batched_problems(w: Workload, batch: int | None = None, N: int | None = None) -> List[Problem]:
     shapes = batched_conv_shapes(w.batch if batch is None else batch, w.seed)
     return [make_problem(w, conv=s, seed=w.seed + b, N=N) for b, s in enumerate(shapes)]

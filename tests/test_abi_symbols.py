@@ -70,6 +70,14 @@ def test_host_side_argument_checks(library):
     assert L.rls_pick_knee(None, 1, 4, 1.05, ctypes.byref(out)) == -2
     d = binding._Domains(9, 4096, 4096)
     assert L.rls_snap_to_valid(fake, 4, 8, 8, ctypes.byref(d), fake, null) == -3   # more knobs than columns
+    d8 = binding._Domains(8, 4096, 4096)
+    assert L.rls_knob_modes(fake, 100, 8, 8, ctypes.byref(d), 40, fake, fake, null) == -3      # more knobs than columns
+    assert L.rls_knob_modes(fake, 100, 8, 8, ctypes.byref(d8), 4, fake, fake, null) == -1      # fewer values than knobs
+    assert L.rls_knob_modes(fake, 100, 8, 8, ctypes.byref(d8), 8193, fake, fake, null) == -1   # above RLS_MAX_DOMAIN_VALUES
+    assert L.rls_knob_modes(fake, 100, 8, 8, ctypes.byref(d8), 40, null, fake, null) == -2
+    assert L.rls_replace_visited(fake, 4, 8, null, 10, fake, fake, null) == -2                  # visited rows missing
+    assert L.rls_replace_visited(fake, 0, 8, fake, 10, fake, fake, null) == -1
+    assert L.rls_replace_visited(fake, 4, 33, fake, 10, fake, fake, null) == -1
 
 
 def test_pick_knee_matches_golden_cases(library):

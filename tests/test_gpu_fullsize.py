@@ -94,6 +94,21 @@ def test_whole_layer_full(rls, orc):
     k_star = rls.pick_knee(J.tolist(), w.k_min, w.k_max, 1.05)
     cfg = rls.snap_to_valid(res.centroids_of(k_star), rls.DeviceDomains(p.dom_offsets, p.dom_values)).cpu().numpy()
     np.testing.assert_array_equal(cfg, orc.snap_to_valid(res.centroids_of(k_star).cpu().numpy(), p.dom_offsets, p.dom_values))
+    # per-dimension mode of the whole trajectory and the replacement of visited samples
+    progress("whole_layer: modes and visited filter")
+    dom = rls.DeviceDomains(p.dom_offsets, p.dom_values)
+    mode, hist = rls.knob_modes(X, dom)
+    mode_o, hist_o = orc.knob_modes(p.X, p.dom_offsets, p.dom_values)
+    np.testing.assert_array_equal(hist.cpu().numpy().astype(np.int64), hist_o)
+    np.testing.assert_array_equal(mode.cpu().numpy(), mode_o)
+    visited = synth.visited_configs(p, 65536, w.seed + 1000)
+    visited[:3] = cfg[:3]
+    cfg_dev = torch.as_tensor(cfg).cuda()
+    flags = rls.replace_visited(cfg_dev, torch.as_tensor(visited).cuda(), mode).cpu().numpy()
+    want_cfg, want_flags = orc.replace_visited(cfg, visited, mode_o)
+    assert want_flags[:3].tolist() == [1, 1, 1]
+    np.testing.assert_array_equal(flags, want_flags)
+    np.testing.assert_array_equal(cfg_dev.cpu().numpy(), want_cfg)
 
 
 @pytest.mark.timeout(900)

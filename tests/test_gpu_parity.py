@@ -104,6 +104,72 @@ def test_snap_irregular_domains_and_batched(rls, orc):
 
 
 # ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,N", [("tiny", None), ("mid", 50001), ("large", 20000)])
+def test_knob_modes_match_oracle(rls, orc, name, N):
+    p = synth.make_problem(synth.WORKLOADS[name], N=N)
+    mode, hist = rls.knob_modes(dev(p.X), rls.DeviceDomains(p.dom_offsets, p.dom_values))
+    mode_o, hist_o = orc.knob_modes(p.X, p.dom_offsets, p.dom_values)
+    np.testing.assert_array_equal(hist.cpu().numpy().astype(np.int64), hist_o)
+    np.testing.assert_array_equal(mode.cpu().numpy(), mode_o)
+
+
+def test_knob_modes_irregular_domains_ties_and_strided_rows(rls, orc):
+    rng = np.random.default_rng(4)
+    sizes = [5, 1, 9, 3]
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    values = np.concatenate([np.sort(rng.uniform(-5, 5, size=s)) for s in sizes]).astype(np.float32)
+    X = rng.uniform(-7, 7, size=(3001, 6)).astype(np.float32)
+    X[:40, 0] = (values[0] + values[1]) / 2          # half-way between two entries (where fp32 holds it exactly or not)
+    wide = np.zeros((3001, 10), dtype=np.float32)
+    wide[:, :6] = X
+    Xd = dev(wide)[:, :6]                            # rows 10 floats apart
+    mode, hist = rls.knob_modes(Xd, rls.DeviceDomains(offsets, values))
+    mode_o, hist_o = orc.knob_modes(X, offsets, values)
+    np.testing.assert_array_equal(hist.cpu().numpy().astype(np.int64), hist_o)
+    np.testing.assert_array_equal(mode.cpu().numpy(), mode_o)
+    # entries in no particular order, with a repeated value: the scan path, first of equal entries wins
+    shuffled = values.copy()
+    shuffled[offsets[2]:offsets[3]] = shuffled[offsets[2]:offsets[3]][::-1]
+    shuffled[offsets[2] + 4] = shuffled[offsets[2] + 1]
+    rep = values.copy()
+    rep[offsets[2] + 3] = rep[offsets[2] + 2]                 # sorted with a repeated value: the bisection path
+    for vals in (shuffled, rep):
+        mode, hist = rls.knob_modes(Xd, rls.DeviceDomains(offsets, vals))
+        mode_o, hist_o = orc.knob_modes(X, offsets, vals)
+        np.testing.assert_array_equal(hist.cpu().numpy().astype(np.int64), hist_o)
+        np.testing.assert_array_equal(mode.cpu().numpy(), mode_o)
+    # equal counts: two entries of one knob, each taken by exactly half of the rows
+    offs2 = np.array([0, 3], dtype=np.int32)
+    vals2 = np.array([0.0, 1.0, 2.0], dtype=np.float32)
+    X2 = np.zeros((1000, 2), dtype=np.float32)
+    X2[::2, 0] = 2.0
+    X2[1::2, 0] = 1.0
+    mode, hist = rls.knob_modes(dev(X2), rls.DeviceDomains(offs2, vals2))
+    assert hist.cpu().tolist() == [0, 500, 500]
+    assert mode.cpu().tolist() == [1]
+
+
+def test_replace_visited_matches_oracle(rls, orc):
+    rng = np.random.default_rng(9)
+    n_knobs = 8
+    visited = rng.integers(0, 2, size=(5000, n_knobs)).astype(np.int32)          # 256 possible rows, most of them visited
+    cfg = rng.integers(0, 2, size=(128, n_knobs)).astype(np.int32)
+    cfg[:16, 0] = 7                                                               # certainly not visited
+    mode = rng.integers(0, 9, size=n_knobs).astype(np.int32)
+    want_cfg, want_flags = orc.replace_visited(cfg, visited, mode)
+    assert 0 < want_flags.sum() < 128
+    cfg_d = dev(cfg.copy())
+    flags = rls.replace_visited(cfg_d, dev(visited), dev(mode))
+    np.testing.assert_array_equal(flags.cpu().numpy(), want_flags)
+    np.testing.assert_array_equal(cfg_d.cpu().numpy(), want_cfg)
+    # nothing visited yet
+    cfg_d = dev(cfg.copy())
+    flags = rls.replace_visited(cfg_d, None, dev(mode))
+    assert int(flags.sum()) == 0
+    np.testing.assert_array_equal(cfg_d.cpu().numpy(), cfg)
+
+
+# ----------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name,N,k_max", [("tiny", None, 16), ("mid", 30000, 40), ("large", 5000, 24)])
 def test_seeding_chain(rls, orc, name, N, k_max):
     p = synth.make_problem(synth.WORKLOADS[name], N=N)
