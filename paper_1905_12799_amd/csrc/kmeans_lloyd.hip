@@ -191,6 +191,26 @@ __device__ inline void split3(float v, unsigned &h, unsigned &m, unsigned &l)
     l = __float_as_uint(r2) >> 16;
 }
 
+// The same exact split for two values at once, with the packed conversion (round to nearest even): each result
+// holds a's piece in its low half and b's in its high half, as two neighbouring operand elements.  With nearest
+// rounding the remainders are even smaller than with truncation (a - h needs 16 bits, a - h - m needs 8), so
+// h + m + l is still exactly the value.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline unsigned cvt_pk_bf16(float a, float b)
+{
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+__device__ inline void split3_pair(float a, float b, unsigned &h, unsigned &m, unsigned &l)
+{
+    h = cvt_pk_bf16(a, b);
+    const float ra = a - __uint_as_float(h << 16), rb = b - __uint_as_float(h & 0xffff0000u);
+    m = cvt_pk_bf16(ra, rb);
+    const float sa = ra - __uint_as_float(m << 16), sb = rb - __uint_as_float(m & 0xffff0000u);
+    l = cvt_pk_bf16(sa, sb);
+}
+
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // The index that phase A packs into the low 7 bits of a key is the centroid index within the run:
@@ -373,12 +393,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             xn[pb] = part + xchg32(part);
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
-                unsigned ph[8], pm[8], pl[8];
+                unsigned ph[4], pm[4], pl[4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) split3(xc[8 * ks + i], ph[i], pm[i], pl[i]);
-                bx[pb][0][ks] = as_bf16x8(make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
-                bx[pb][1][ks] = as_bf16x8(make_uint4(pm[0] | (pm[1] << 16), pm[2] | (pm[3] << 16), pm[4] | (pm[5] << 16), pm[6] | (pm[7] << 16)));
-                bx[pb][2][ks] = as_bf16x8(make_uint4(pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16), pl[4] | (pl[5] << 16), pl[6] | (pl[7] << 16)));
+                for (int i = 0; i < 4; ++i) split3_pair(xc[8 * ks + 2 * i], xc[8 * ks + 2 * i + 1], ph[i], pm[i], pl[i]);
+                bx[pb][0][ks] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                bx[pb][1][ks] = as_bf16x8(make_uint4(pm[0], pm[1], pm[2], pm[3]));
+                bx[pb][2][ks] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
             }
             unsigned nh, nm, nl;
             split3(xn[pb], nh, nm, nl);

@@ -325,6 +325,35 @@ def test_sweep_batched(rls, orc):
         compare_sweep(orc, p.X, one, ref, 1, 32)
 
 
+def test_sweep_strided_unaligned_rows_and_small_d(rls, orc):
+    # rows 11 floats apart and starting 4 bytes off a 16-byte boundary: the scalar load paths
+    rng = np.random.default_rng(21)
+    for d in (1, 3, 7, 8):
+        X = (rng.integers(0, 5, size=(1100, d)) * 3.0 + rng.standard_normal((1100, d))).astype(np.float32)
+        buf = torch.zeros(1100 * 11 + 1, dtype=torch.float32, device="cuda")
+        Xd = buf[1:].view(1100, 11)[:, :d]
+        Xd.copy_(torch.as_tensor(X))
+        res = rls.kmeans_sweep(Xd, 1, 11, 4, seed=4, want_trace=True)
+        ref = orc.kmeans_sweep(X, 1, 11, 4, seed=4, want_trace=True)
+        torch.cuda.synchronize()
+        assert compare_sweep(orc, X, res, ref, 1, 11) == 0
+
+
+def test_sweep_wide_columns(rls, orc):
+    # one column mixes values near 2^-10 and near 2^40 with full 24-bit significands: more binary digits than the
+    # main fixed-point accumulator keeps, so the low-order accumulator is in play; sums must still be exact
+    rng = np.random.default_rng(22)
+    N = 3000
+    X = rng.standard_normal((N, 8)).astype(np.float32)
+    small = rng.integers(1, 1 << 24, size=N).astype(np.float64) * 2.0 ** -34
+    big = rng.integers(1, 1 << 24, size=N).astype(np.float64) * 2.0 ** 16
+    X[:, 2] = np.where(rng.random(N) < 0.5, small, big).astype(np.float32)
+    X[:, 5] = (rng.integers(-(1 << 23), 1 << 23, size=N).astype(np.float64) * 2.0 ** -30).astype(np.float32)
+    res, ref = run_both(rls, orc, X, 1, 9, 5, seed=6)
+    assert int(res.status.item()) == 0
+    assert compare_sweep(orc, X, res, ref, 1, 9) == 0
+
+
 def test_sweep_status_flags(rls):
     X = np.ones((600, 8), dtype=np.float32)
     X[5, 2] = np.inf
