@@ -512,11 +512,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const int k1 = m1[pb][st], k2 = m2[pb][st], k3 = m3[pb][st];
                 const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
                 const float f3 = __int_as_float(k3 & (int)0xffffff80);
-                // error bound of the expansion (rounding of norms, products and the centring) plus the
-                // 7 mantissa bits given up to the index in each key
+                // error bound of the two expansions (rounding of norms, products and the centring) plus the 7
+                // mantissa bits given up to the index: a key is its value cut down by less than 2^-16 of itself,
+                // so the smaller key's value may lie that much higher (2^-15 here)
                 const float tol0 = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 1.0e-30f;
-                const bool close = active && !(f2 - f1 > tol0 + 6.2e-5f * fabsf(f2));
-                const bool clear3 = f3 - f1 > tol0 + 6.2e-5f * fabsf(f3);
+                const bool close = active && !(f2 - f1 > tol0 + 3.0517578125e-5f * fabsf(f2));
+                const bool clear3 = f3 - f1 > tol0 + 3.0517578125e-5f * fabsf(f3);
                 pend2 |= (unsigned)(close && clear3) << (pb * ST + st);
                 pend3 |= (unsigned)(close && !clear3) << (pb * ST + st);
             }
@@ -785,9 +786,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     c.chunk_end = min(a.N, c.chunk_begin + plan.chunk_len);
     // 16-byte loads need whole quads of features and aligned rows
     c.vec_x = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
-    // bound on the error of the matrix-pipeline distances relative to |x'|^2 + |c'|^2: dropped piece products
-    // (2^-23), seven chained fp32 accumulations of up to 16 products each, rounding of the norms and of the centring
-    c.eps_a = (float)(8 * (DP + 8)) * 1.1920928955078125e-07f;   // 8 (DP + 8) 2^-23
+    // Bound on the summed error of two matrix-pipeline distances, relative to S = |x'|^2 + max |c'|^2.  Per
+    // distance: dropped piece products 2^-23 S; 7 or 13 chained MFMAs, each charged five fp32 roundings of a
+    // partial sum of at most 2 S (35 or 65 times 2^-23 S); fp32 norms d_pad 2^-24 S each; centring 2 2^-23 S:
+    // 46 2^-23 S at d_pad <= 16 and 84 2^-23 S at 32.  Twice that is 92 and 168; the bound used is 120 and 200.
+    c.eps_a = (float)(5 * ((DP < 16 ? 16 : DP) + 8)) * 1.1920928955078125e-07f;   // 5 (max(DP, 16) + 8) 2^-23
 
     double jloc[8];
 #pragma unroll
