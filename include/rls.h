@@ -23,7 +23,7 @@
  *   - Argument errors are detected on the host before anything is enqueued.  Conditions that
  *     only the data can reveal (see rls_kmeans_sweep) are reported through `status_dev`.
  *   - Limits: 1 <= d <= RLS_MAX_D, k_max <= RLS_MAX_K, tree depth <= RLS_MAX_DEPTH,
- *     N <= RLS_MAX_N, batch <= RLS_MAX_BATCH.
+ *     N <= RLS_MAX_N, batch <= RLS_MAX_BATCH; rls_kmeans_sweep also needs ldx <= RLS_MAX_LDX.
  */
 #ifndef RLS_H
 #define RLS_H
@@ -47,6 +47,7 @@ extern "C" {
 #define RLS_MAX_DEPTH 12
 #define RLS_MAX_N (1LL << 26)
 #define RLS_MAX_BATCH 1024
+#define RLS_MAX_LDX (1 << 24)       /* leading dimension of X accepted by rls_kmeans_sweep (elements) */
 
 /* bits of *status_dev written by rls_kmeans_sweep (0 = clean) */
 #define RLS_STATUS_NONFINITE 1     /* X holds an infinity or NaN */

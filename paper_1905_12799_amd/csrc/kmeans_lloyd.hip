@@ -19,6 +19,8 @@
 //            equal a fresh sum in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel
 //            adds them to the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
 // The final pass replaces the update by the fp64 loss of every point and the label output.
+#include <type_traits>
+
 #include "rls_internal.h"
 
 namespace rls {
@@ -306,6 +308,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     constexpr int NS = tile_slots_of(DP);           // operand slots per tile and lane
     constexpr int HP = 8 * NK;                      // feature slots per half-wave (H padded to whole K-steps)
     constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);   // runs owned by a lane
+    constexpr int SLAB_ = 32 * NB;                  // points a wave takes at a time
     constexpr int NM = 6 * NK + 1;                  // MFMAs per tile block
     constexpr int VPER = (64 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
     constexpr bool LOSS = FINAL || TRACE;
@@ -323,21 +326,29 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     // Raw features of this lane's half of its points.  The rows of the next step are loaded while this step
     // runs: the loads are unconditional (addresses clamped into the chunk and the row, masking happens when the
     // values are used) and nothing touches their registers before settle(), so no wait is placed early.
+    // Addresses are a wave-uniform base (the slab's first row) plus a 32-bit lane offset: the row index inside
+    // the slab is clamped to the chunk's last row, the feature offset to the row's last 16 bytes.
     float xnext[NB][HP];
-    auto fetch = [&](int64_t p0) {
+    const unsigned ldx32 = (unsigned)c.ldx;          // checked on the host: 64 rows of ldx floats fit 32 bits
+    unsigned foff[H];                                // this lane's clamped feature offsets (fixed for the launch)
+#pragma unroll
+    for (int s = 0; s < H; ++s) foff[s] = (unsigned)(c.vec_x ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1));
+    auto fetch = [&](int64_t slab_base) {
+        const float *Xs = c.X + slab_base * c.ldx;
+        const unsigned last = (unsigned)min((int64_t)(SLAB_ - 1), c.chunk_end - 1 - slab_base);
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const int64_t p = min(p0 + pb * 32 + n, c.chunk_end - 1);
-            const float *row = c.X + p * c.ldx;
+            const unsigned li = min((unsigned)(pb * 32 + n), last);
+            const unsigned ro = li * ldx32;
             if (c.vec_x) {
 #pragma unroll
                 for (int c4 = 0; c4 < H / 4; ++c4) {
-                    const float4 v = *reinterpret_cast<const float4 *>(row + min(f0 + 4 * c4, d - 4));
+                    const float4 v = *reinterpret_cast<const float4 *>(Xs + (ro + foff[4 * c4]));
                     xnext[pb][4 * c4 + 0] = v.x; xnext[pb][4 * c4 + 1] = v.y; xnext[pb][4 * c4 + 2] = v.z; xnext[pb][4 * c4 + 3] = v.w;
                 }
             } else {
 #pragma unroll
-                for (int s = 0; s < H; ++s) xnext[pb][s] = row[min(f0 + s, d - 1)];
+                for (int s = 0; s < H; ++s) xnext[pb][s] = Xs[ro + foff[s]];
             }
         }
     };
@@ -350,7 +361,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     };
     // The chunk is handed out in slabs of SLAB points: the first eight statically, the rest from a counter in
     // LDS, so the waves of the workgroup finish together however their close calls and updates are spread.
-    constexpr int SLAB = 32 * NB;
+    constexpr int SLAB = SLAB_;
     const int n_slabs = (int)((c.chunk_end - c.chunk_begin + SLAB - 1) / SLAB);
     auto grab = [&]() -> int {
         int v = 0;
@@ -381,6 +392,9 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         float xn[NB];
         int m1[NB][ST], m2[NB][ST], m3[NB][ST];
         int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
+        unsigned poff[NB][ST];            // offset of the pair's label behind the slab's first point (runs are N apart)
+        unsigned char *prev_slab = c.prev + base;
+        const unsigned slab_last = (unsigned)min((int64_t)(SLAB - 1), c.chunk_end - 1 - base);
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             float xc[HP];
@@ -404,13 +418,13 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             split3(xn[pb], nh, nm, nl);
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
             // labels these (point, run) pairs had in the previous round, 0xff before the first one (the loads
-            // complete during the tile loop)
-            const int64_t p = base + pb * 32 + n;
+            // complete during the tile loop); same addressing: uniform base of the slab, 32-bit lane offset
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; m3[pb][st] = kBigKey;
-                const int rl = S == 8 ? 0 : hl * ST + st;
-                oldl[pb][st] = FINAL ? 0xff : (int)c.prev[(int64_t)min(rl, c.n_runs - 1) * c.N + min(p, c.chunk_end - 1)];
+                const unsigned rl = S == 8 ? 0u : (unsigned)(hl * ST + st);
+                poff[pb][st] = min(rl, (unsigned)(c.n_runs - 1)) * (unsigned)c.N + min((unsigned)(pb * 32 + n), slab_last);
+                oldl[pb][st] = FINAL ? 0xff : (int)prev_slab[poff[pb][st]];
             }
         }
 
@@ -423,12 +437,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
         };
         load_a(a_even, 0);
-        const float big = __int_as_float(kBigKey);
-        floatx16 acc_prev = {big, big, big, big, big, big, big, big, big, big, big, big, big, big, big, big};
+        floatx16 acc_prev;                 // results of the block before the current one, folded one block late
         int kidx_old[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) kidx_old[e] = 0;
-        auto tile_step = [&](const bf16x8 (&a_cur)[NS], bf16x8 (&a_nxt)[NS], int t) {
+        // `first`: the very first block of the slab has no block before it to fold
+        auto tile_step = [&](const bf16x8 (&a_cur)[NS], bf16x8 (&a_nxt)[NS], int t, auto first) {
             load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
             // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
             int kidx[16];
@@ -454,8 +466,11 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
-                if (pb == 0) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
-                else fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1], m3[pb - 1]);
+                if (pb == 0) {
+                    if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+                } else {
+                    fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1], m3[pb - 1]);
+                }
 #pragma unroll
                 for (int s = 0; s < NM; ++s) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
@@ -467,12 +482,13 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
         };
         {
-            int t = 0;
+            tile_step(a_even, a_odd, 0, std::true_type{});
+            int t = 1;
             for (; t + 2 <= c.n_tiles; t += 2) {
-                tile_step(a_even, a_odd, t);
-                tile_step(a_odd, a_even, t + 1);
+                tile_step(a_odd, a_even, t, std::false_type{});
+                tile_step(a_even, a_odd, t + 1, std::false_type{});
             }
-            if (t < c.n_tiles) tile_step(a_even, a_odd, t);
+            if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
         }
         fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
         // the next rows have arrived by now; asking for them here, before this step's stores are issued,
@@ -618,10 +634,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
                 const int lab = m1[pb][st] & 127;
                 if (FINAL) {
-                    if (active && c.labels_out) c.labels_out[(int64_t)rl * c.N + p] = lab;
+                    if (active && c.labels_out) (c.labels_out + base)[poff[pb][st]] = lab;
                 } else {
                     const bool moved = active && lab != oldl[pb][st];
-                    if (moved) c.prev[(int64_t)rl * c.N + p] = (unsigned char)lab;
+                    if (moved) prev_slab[poff[pb][st]] = (unsigned char)lab;
                     mv |= (unsigned)moved << (pb * ST + st);
                 }
             }

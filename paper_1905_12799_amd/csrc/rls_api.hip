@@ -173,6 +173,7 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
     if (!centroids_dev || !inertia_dev || !status_dev) return RLS_ERR_NULL;
     if (!init_idx_dev && !seeds) return RLS_ERR_NULL;
     if (iters < 0) return RLS_ERR_INVALID_ARG;
+    if (ldx > RLS_MAX_LDX) return RLS_ERR_SHAPE;   // the step kernel addresses a slab of rows with 32-bit offsets
     if (batch > 1 && x_batch_stride < N * ldx - (ldx - d)) return RLS_ERR_SHAPE;
     SweepPlan plan;
     rc = make_sweep_plan(N, d, k_min, k_max, batch, &plan);

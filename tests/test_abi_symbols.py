@@ -65,6 +65,7 @@ def test_host_side_argument_checks(library):
     assert L.rls_kmeans_sweep(fake, 1000, 8, 8, 1, 16, 5, seed, null, null, fake, fake, null, fake, null, 0, null) == -4
     assert L.rls_kmeans_sweep(fake, 1000, 8, 8, 1, 16, 5, seed, null, null, fake, fake, null, fake, fake, 16, null) == -4
     assert L.rls_kmeans_sweep(fake, 1000, 8, 8, 1, 16, -1, seed, null, null, fake, fake, null, fake, fake, 1 << 40, null) == -1
+    assert L.rls_kmeans_sweep(fake, 1000, 8, (1 << 24) + 1, 1, 16, 5, seed, null, null, fake, fake, null, fake, fake, 1 << 40, null) == -3
     assert L.rls_kmeans_sweep(fake, 1000, 8, 8, 1, 16, 5, seed, null, null, null, fake, null, fake, fake, 1 << 40, null) == -2
     out = ctypes.c_int32(0)
     assert L.rls_pick_knee(None, 1, 4, 1.05, ctypes.byref(out)) == -2
