@@ -75,6 +75,7 @@ struct StepArgs {
     char *ws;                // workspace base
     int64_t ws_bs;           // bytes per batch element
     int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev;
+    int32_t first_round;     // 1: no point has a label yet (every pair enters a cluster, nothing leaves one)
 };
 
 // x * 2^shift truncated toward zero, |x * 2^shift| < 2^kGridBits; exact whenever x is a multiple of 2^-shift.
@@ -283,6 +284,7 @@ struct WaveCtx {
     int64_t chunk_begin, chunk_end;
     int *next_slab;               // LDS: next slab of the chunk to hand out
     bool vec_x;                   // rows of X may be read 16 bytes at a time
+    bool first_round;             // no point has a label yet
     float eps_a;
 };
 
@@ -648,6 +650,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             // one.  Both lanes of the point's pair take part (each holds half of the features); one pair per pass.
             const unsigned mvo = xchg32(mv);
             unsigned both = hl ? (mvo | (mv << NBST)) : (mv | (mvo << NBST));
+            // bits below the grid of a wide column go to a global integer accumulator (rare)
+            auto add_low = [&](int64_t p, int rowbase, int ol, int nl) {
+                const int64_t crow = c.grow0 + rowbase;
+                for (int s = 0; s < nf; ++s) {
+                    if (c.wide_s[f0 + s] == 0) continue;
+                    const long long lo = fixed_low(c.X[p * c.ldx + f0 + s], c.shift_s[f0 + s]);
+                    if (lo == 0) continue;
+                    if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + f0 + s]), (unsigned long long)(-lo));
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + f0 + s]), (unsigned long long)lo);
+                }
+            };
             if (__ballot(both != 0u) != 0ull) {
                 // this lane's half of its points' rows on the fixed-point grid (zero beyond the last feature)
                 long long fx[NB][H];
@@ -655,7 +668,31 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
                     for (int s = 0; s < H; ++s) fx[pb][s] = to_fixed(xraw[pb][s], c.shift_s[f0 + s]);   // xraw is 0 past the last feature
-                do {
+                if (c.first_round) {
+                    // no point has a label yet: every pair of the slab enters its cluster, run by run
+#pragma unroll
+                    for (int pb = 0; pb < NB; ++pb) {
+                        const int64_t p = base + pb * 32 + n;
+                        const bool pvalid = p < c.chunk_end;
+                        for (int r = 0; r < c.n_runs; ++r) {
+                            const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
+                            int nl = 0;
+#pragma unroll
+                            for (int st = 0; st < ST; ++st)
+                                if (st == ost) nl = m1[pb][st] & 127;
+                            const int nlo = xchg32(nl);
+                            if (hl != oh) nl = nlo;
+                            const int rowbase = r * c.k0 + r * (r - 1) / 2;
+                            if (pvalid) {
+                                unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+#pragma unroll
+                                for (int s = 0; s < H; ++s) atomicAdd(sn + s, (unsigned long long)fx[pb][s]);
+                                if (hl == 0) atomicAdd(&c.cnts[rowbase + nl], 1);
+                                if (any_wide) add_low(p, rowbase, 0xff, nl);
+                            }
+                        }
+                    }
+                } else do {
                     const bool act = both != 0u;
                     const int bit = act ? __ffs(both) - 1 : 0;
                     both &= both - 1u;
@@ -687,18 +724,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                             for (int s = 0; s < H; ++s) atomicAdd(so + s, (unsigned long long)(-v[s]));
                             if (hl == 0) atomicAdd(&c.cnts[rowbase + ol], -1);
                         }
-                        if (any_wide) {
-                            // rare: bits below the grid of a wide column go to a global integer accumulator
-                            const int64_t p = base + pb * 32 + n;
-                            const int64_t crow = c.grow0 + rowbase;
-                            for (int s = 0; s < nf; ++s) {
-                                if (c.wide_s[f0 + s] == 0) continue;
-                                const long long lo = fixed_low(c.X[p * c.ldx + f0 + s], c.shift_s[f0 + s]);
-                                if (lo == 0) continue;
-                                if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + f0 + s]), (unsigned long long)(-lo));
-                                atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + f0 + s]), (unsigned long long)lo);
-                            }
-                        }
+                        if (any_wide) add_low(base + pb * 32 + n, rowbase, ol, nl);
                     }
                 } while (__ballot(both != 0u) != 0ull);
             }
@@ -801,6 +827,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     c.chunk_begin = (int64_t)chunk * plan.chunk_len;
     c.chunk_end = min(a.N, c.chunk_begin + plan.chunk_len);
     // 16-byte loads need whole quads of features and aligned rows
+    c.first_round = a.first_round != 0;
     c.vec_x = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
     // Bound on the summed error of two matrix-pipeline distances, relative to S = |x'|^2 + max |c'|^2.  Per
     // distance: dropped piece products 2^-23 S; 7 or 13 chained MFMAs, each charged five fp32 roundings of a
@@ -1269,6 +1296,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     const bool trace = a.trace != nullptr;
     const bool prof = profile_enabled();
     for (int t = 0; t < a.iters; ++t) {
+        sa.first_round = t == 0 ? 1 : 0;
         if (prof) { hipError_t e = profile_mark(s, true); if (e != hipSuccess) return e; }
         if (trace) {
             hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(kThreads), lds, s, plan, sa);
