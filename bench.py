@@ -25,6 +25,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix
 
+# HBM bytes of one lloyd_step_kernel launch from rocprofv3 counters (profiles/lloyd_step_whole_layer_hbm_counters.md):
+# FETCH_SIZE / WRITE_SIZE in KiB per dispatch and the factors a plain 1 GiB copy gives for each counter.  Valid
+# only for the library version the counters were taken with; any other version reports traffic = null.
+HBM_COUNTERS = {
+    "whole_layer": {"version": 101, "fetch_kib": 330503.7, "write_kib": 54345.2, "fetch_scale": 2.0, "write_scale": 1.0},
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -162,6 +169,13 @@ def main() -> int:
     else:
         roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+    hc = HBM_COUNTERS.get(w.name)
+    if hc is not None and hc["version"] == rls.version() and want_labels:
+        hbm_bytes = (hc["fetch_kib"] * hc["fetch_scale"] + hc["write_kib"] * hc["write_scale"]) * 1024.0
+        # same unit as `achieved` when the bound is HBM; the ratio to the algorithmic bytes is what matters
+        roofline["traffic"] = hbm_bytes / (kernel_ms * 1e-3) / 1e9
+        roofline["traffic_bytes_per_launch"] = hbm_bytes
+    roofline["algorithmic_bytes_per_launch"] = alg_bytes
     roofline.update({"kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_ms,
                      "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
                      "algorithmic_TFLOPs": tflops, "mfma_f32_frac": tflops / MFMA_F32_PEAK_TFLOPS})
