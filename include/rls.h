@@ -199,7 +199,7 @@ int32_t rls_knob_modes(const float *X_dev, int64_t N, int32_t d, int64_t ldx, co
 /*
  * The last loop of Algorithm 1: a sample that is already among the visited configurations v_Theta is
  * replaced by mode(s_Theta).  Configurations are rows of n_knobs domain indices.
- *   cfg_dev      [k][n_knobs] int32, updated in place
+ *   cfg_dev      [k][n_knobs] int32, updated in place; 1 <= k <= 65535
  *   visited_dev  [n_visited][n_knobs] int32 (may be null when n_visited == 0)
  *   mode_cfg_dev [n_knobs] int32
  *   replaced_dev [k] int32 (written): 1 where the row was replaced

@@ -8,7 +8,8 @@
 //                    ballot when the knob has only a few; the workgroup then adds its counts to the global
 //                    histogram (integer atomics: the result does not depend on the order).
 // knob_mode_kernel   one thread per knob: first maximum of its slice of the histogram.
-// replace_visited_kernel  one workgroup per sample: its threads compare the sample with the visited rows.
+// visited_scan_kernel / visited_apply_kernel  workgroups compare one sample with a slice of the visited rows and
+//                    flag it; flagged samples are then overwritten with the mode.
 #include "rls_internal.h"
 
 namespace rls {
@@ -111,28 +112,33 @@ __global__ void knob_mode_kernel(DomainArgs dm, const int32_t *__restrict__ hist
     mode_cfg[j] = arg - lo;
 }
 
-__global__ void __launch_bounds__(kHistThreads) replace_visited_kernel(int32_t *__restrict__ cfg, int n_knobs,
-                                                                        const int32_t *__restrict__ visited, int64_t n_visited,
-                                                                        const int32_t *__restrict__ mode_cfg,
-                                                                        int32_t *__restrict__ replaced)
+// grid (slices of the visited rows, samples): a workgroup compares one sample with its slice of v_Theta
+__global__ void __launch_bounds__(kHistThreads) visited_scan_kernel(const int32_t *__restrict__ cfg, int n_knobs,
+                                                                     const int32_t *__restrict__ visited, int64_t n_visited,
+                                                                     int64_t slice, int32_t *__restrict__ replaced)
 {
     __shared__ int mine[kMaxKnobs];
-    __shared__ int found;
-    const int i = blockIdx.x, tid = threadIdx.x;
+    const int i = blockIdx.y, tid = threadIdx.x;
     if (tid < n_knobs) mine[tid] = cfg[(int64_t)i * n_knobs + tid];
-    if (tid == 0) found = 0;
     __syncthreads();
+    const int64_t v0 = (int64_t)blockIdx.x * slice, v1 = min(n_visited, v0 + slice);
     int hit = 0;
-    for (int64_t v = tid; v < n_visited; v += kHistThreads) {
+    for (int64_t v = v0 + tid; v < v1; v += kHistThreads) {
         const int32_t *row = visited + v * n_knobs;
         int same = 1;
         for (int j = 0; j < n_knobs; ++j) same &= (row[j] == mine[j]) ? 1 : 0;
         hit |= same;
     }
-    if (hit) atomicOr(&found, 1);
-    __syncthreads();
-    if (tid == 0) replaced[i] = found;
-    if (found && tid < n_knobs) cfg[(int64_t)i * n_knobs + tid] = mode_cfg[tid];
+    if (__ballot(hit != 0) != 0ull && (tid & 63) == 0) atomicOr(&replaced[i], 1);
+}
+
+// one thread per (sample, knob): visited samples take the mode
+__global__ void visited_apply_kernel(int32_t *__restrict__ cfg, int k, int n_knobs, const int32_t *__restrict__ mode_cfg,
+                                     const int32_t *__restrict__ replaced)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= k * n_knobs) return;
+    if (replaced[e / n_knobs]) cfg[e] = mode_cfg[e % n_knobs];
 }
 
 }  // namespace
@@ -158,7 +164,20 @@ hipError_t launch_knob_modes(const float *X, int64_t N, int64_t ldx, const Domai
 hipError_t launch_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, const int32_t *visited, int64_t n_visited,
                                   const int32_t *mode_cfg, int32_t *replaced, hipStream_t s)
 {
-    hipLaunchKernelGGL(replace_visited_kernel, dim3(k), dim3(kHistThreads), 0, s, cfg, (int)n_knobs, visited, n_visited,
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((k + 255) / 256), dim3(256), 0, s, replaced, (int)k);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_visited == 0) return e;
+    // slices of at least 4096 rows, at most ~1024 workgroups in all
+    int64_t slices = (n_visited + 4095) / 4096;
+    const int64_t cap = (1024 + k - 1) / k;
+    if (slices > cap) slices = cap;
+    if (slices < 1) slices = 1;
+    const int64_t slice = (n_visited + slices - 1) / slices;
+    hipLaunchKernelGGL(visited_scan_kernel, dim3((unsigned)slices, (unsigned)k), dim3(kHistThreads), 0, s, cfg, (int)n_knobs,
+                       visited, n_visited, slice, replaced);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(visited_apply_kernel, dim3((k * n_knobs + 255) / 256), dim3(256), 0, s, cfg, (int)k, (int)n_knobs,
                        mode_cfg, replaced);
     return hipGetLastError();
 }

@@ -269,7 +269,7 @@ int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const 
                             int64_t n_visited, const int32_t *mode_cfg_dev, int32_t *replaced_dev, void *stream)
 {
     if (!cfg_dev || !mode_cfg_dev || !replaced_dev) return RLS_ERR_NULL;
-    if (k < 1 || n_knobs < 1 || n_knobs > RLS_MAX_D || n_visited < 0) return RLS_ERR_INVALID_ARG;
+    if (k < 1 || k > 65535 || n_knobs < 1 || n_knobs > RLS_MAX_D || n_visited < 0) return RLS_ERR_INVALID_ARG;
     if (n_visited > 0 && !visited_dev) return RLS_ERR_NULL;
     RLS_HIP_TRY(launch_replace_visited(cfg_dev, k, n_knobs, visited_dev, n_visited, mode_cfg_dev, replaced_dev,
                                        (hipStream_t)stream));
