@@ -194,6 +194,19 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    if not batched:
+        # Algorithm 1 with its early exit at the knee (k in waves of 8), outside the timed steps: same chosen k,
+        # only the waves up to the knee are computed
+        k_e, n_done, _ = rls.kmeans_sweep_until_knee(X, w.k_min, w.k_max, 8, w.iters, knee_const, seed=seeds[0],
+                                                     want_labels=want_labels)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(3):
+            k_e, n_done, _ = rls.kmeans_sweep_until_knee(X, w.k_min, w.k_max, 8, w.iters, knee_const, seed=seeds[0],
+                                                         want_labels=want_labels)
+        torch.cuda.synchronize()
+        out["early_exit"] = {"ms": (time.perf_counter() - t2) * 1e3 / 3, "chosen_k": k_e, "k_computed": n_done, "k_wave": 8}
+
     if not args.no_cpu_baseline:
         import oracle
         p0 = probs[0]

@@ -8,6 +8,7 @@
  *   rls_gbt_score       predicted fitness of every configuration of a trajectory
  *   rls_kmeans_sweep    k-means(s_Theta, k) for every k of a range: centroids, clusters, loss
  *   rls_pick_knee       the knee test on the loss curve (host, scalar)
+ *   rls_kmeans_sweep_until_knee  the same loop with Algorithm 1's early exit at the knee
  *   rls_snap_to_valid   NextSamples = Centroids, as valid configurations
  *   rls_knob_modes      mode(s_Theta), dimension by dimension
  *   rls_replace_visited samples already in v_Theta give way to mode(s_Theta)
@@ -18,7 +19,8 @@
  *     pointers.  The library never allocates or frees device memory: scratch space comes in
  *     through `workspace_dev`, sized by the matching *_workspace_bytes query.
  *   - `stream` is a hipStream_t passed as void*.  Calls enqueue kernels on it and return
- *     without synchronising; outputs are valid once the stream has drained.
+ *     without synchronising; outputs are valid once the stream has drained.  The one exception,
+ *     rls_kmeans_sweep_until_knee, says so.
  *   - Matrices are row-major fp32 with an explicit leading dimension in elements.
  *   - Argument errors are detected on the host before anything is enqueued.  Conditions that
  *     only the data can reveal (see rls_kmeans_sweep) are reported through `status_dev`.
@@ -147,6 +149,28 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
                                  const uint64_t *seeds, const int64_t *init_idx_dev, int32_t *labels_dev,
                                  float *centroids_dev, double *inertia_dev, double *inertia_trace_dev,
                                  int32_t *status_dev, void *workspace_dev, int64_t workspace_bytes, void *stream);
+
+/*
+ * Algorithm 1's loop as it is written: k-means for k = k_min, k_min + 1, ... until the knee test fires, then stop.
+ * The k are taken k_wave at a time (one sweep per wave, its k side by side as in rls_kmeans_sweep); after each wave
+ * this call SYNCHRONISES `stream`, copies the wave's losses to inertia_host and applies the test of rls_pick_knee in
+ * k order.  The outputs for the k that were computed equal those of rls_kmeans_sweep over the whole range, and
+ * *k_out equals rls_pick_knee on the whole curve: runs for different k do not depend on each other.
+ *   k_wave        >= 1; a multiple of 8 keeps the MFMA tiles full
+ *   seed / init_idx_dev  as rls_kmeans_sweep (the chain is extended wave by wave)
+ *   labels_dev    [k_max-k_min+1][N] or null; centroids_dev, inertia_dev as rls_kmeans_sweep; only the first
+ *                 *n_done_out runs are written
+ *   inertia_host  [k_max-k_min+1] fp64 (host), first *n_done_out entries written
+ *   k_out         the chosen k (k_max when the test never fires; 0 when *status_dev != 0)
+ *   n_done_out    how many k were computed (a whole number of waves, or all)
+ * Workspace: rls_kmeans_sweep_until_knee_workspace_bytes.
+ */
+int64_t rls_kmeans_sweep_until_knee_workspace_bytes(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t k_wave);
+int32_t rls_kmeans_sweep_until_knee(const float *X_dev, int64_t N, int32_t d, int64_t ldx, int32_t k_min, int32_t k_max,
+                                    int32_t k_wave, int32_t iters, uint64_t seed, const int64_t *init_idx_dev,
+                                    double knee_const, int32_t *labels_dev, float *centroids_dev, double *inertia_dev,
+                                    double *inertia_host, int32_t *k_out, int32_t *n_done_out, int32_t *status_dev,
+                                    void *workspace_dev, int64_t workspace_bytes, void *stream);
 
 /*
  * Knee of the loss curve (Algorithm 1): with PreviousLoss = infinity, walk k upward and stop at the

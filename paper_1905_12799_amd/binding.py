@@ -65,6 +65,12 @@ def lib() -> ctypes.CDLL:
         L.rls_kmeans_sweep_batched.restype = i32
         L.rls_kmeans_sweep_batched.argtypes = [i32, vp, i64, i32, i64, i64, i32, i32, i32, ctypes.POINTER(u64), vp, vp,
                                                vp, vp, vp, vp, vp, i64, vp]
+        L.rls_kmeans_sweep_until_knee_workspace_bytes.restype = ctypes.c_int64
+        L.rls_kmeans_sweep_until_knee_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+        L.rls_kmeans_sweep_until_knee.restype = i32
+        L.rls_kmeans_sweep_until_knee.argtypes = [vp, i64, i32, i64, i32, i32, i32, i32, u64, vp, f64, vp, vp, vp,
+                                                  ctypes.POINTER(f64), ctypes.POINTER(i32), ctypes.POINTER(i32), vp, vp,
+                                                  i64, vp]
         L.rls_pick_knee.restype = i32
         L.rls_pick_knee.argtypes = [ctypes.POINTER(f64), i32, i32, f64, ctypes.POINTER(i32)]
         L.rls_snap_to_valid.restype = i32
@@ -249,6 +255,45 @@ def kmeans_sweep(X: torch.Tensor, k_min: int, k_max: int, iters: int, seed: int 
         if st != 0:
             raise RuntimeError(f"rls_kmeans_sweep: data precondition violated, status bits {st}")
     return SweepResult(k_min, k_max, d, labels, centroids, inertia, trace, status)
+
+
+def kmeans_sweep_until_knee(X: torch.Tensor, k_min: int, k_max: int, k_wave: int, iters: int, knee_const: float,
+                            seed: int = 0, init_idx: Optional[torch.Tensor] = None, want_labels: bool = True,
+                            workspace: Optional[torch.Tensor] = None) -> Tuple[int, int, SweepResult]:
+    """Algorithm 1's loop with its early exit: returns (chosen k, number of k computed, results).
+
+    The result arrays are sized for the whole range; only the first `n_done` runs are written. Synchronises the
+    current stream after every wave of k_wave values of k."""
+    _mat(X, "X")
+    N, d = X.shape
+    n_k = k_max - k_min + 1
+    rows = sum(range(k_min, k_max + 1))
+    need = int(lib().rls_kmeans_sweep_until_knee_workspace_bytes(N, d, k_min, k_max, k_wave))
+    if need < 0:
+        _check(need, "rls_kmeans_sweep_until_knee_workspace_bytes")
+    ws = _workspace(need, X.device) if workspace is None else workspace
+    dev = X.device
+    labels = torch.empty((n_k, N), dtype=torch.int32, device=dev) if want_labels else None
+    centroids = torch.empty(rows * d, dtype=torch.float32, device=dev)
+    inertia = torch.empty(n_k, dtype=torch.float64, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    if init_idx is not None:
+        _dev(init_idx, torch.int64, "init_idx")
+        if init_idx.numel() < k_max:
+            raise ValueError("init_idx needs k_max entries")
+    inertia_host = (ctypes.c_double * n_k)()
+    k_out, n_done = ctypes.c_int32(0), ctypes.c_int32(0)
+    base = _aligned_ptr(ws)
+    avail = ws.numel() - (base - ws.data_ptr())
+    rc = lib().rls_kmeans_sweep_until_knee(_ptr(X), N, d, X.stride(0), k_min, k_max, k_wave, iters, ctypes.c_uint64(seed),
+                                           _ptr(init_idx), float(knee_const), _ptr(labels), _ptr(centroids), _ptr(inertia),
+                                           inertia_host, ctypes.byref(k_out), ctypes.byref(n_done), _ptr(status),
+                                           ctypes.c_void_p(base), avail, _stream())
+    _check(rc, "rls_kmeans_sweep_until_knee")
+    st = int(status.item())
+    if st != 0:
+        raise RuntimeError(f"rls_kmeans_sweep_until_knee: data precondition violated, status bits {st}")
+    return int(k_out.value), int(n_done.value), SweepResult(k_min, k_max, d, labels, centroids, inertia, None, status)
 
 
 def kmeans_sweep_batched(X: torch.Tensor, k_min: int, k_max: int, iters: int, seeds: Optional[Sequence[int]] = None,

@@ -199,14 +199,16 @@ __global__ void __launch_bounds__(1024) seed_pick_kernel(SeedList seeds, int b0,
 hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
                              int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
                              double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,
-                             int32_t seed_blocks, hipStream_t s)
+                             int32_t seed_blocks, hipStream_t s, int32_t j_begin)
 {
+    // positions j_begin .. k_max-1 of the chain are produced; the distance state of an earlier call for the same
+    // chain (positions 0 .. j_begin-1) must still be in `mind`
     for (int b0 = 0; b0 < batch; b0 += 64) {
         const int nb = batch - b0 < 64 ? batch - b0 : 64;
         SeedList sl;
         for (int i = 0; i < 64; ++i) sl.seed[i] = seeds_host[b0 + (i < nb ? i : 0)];
-        hipLaunchKernelGGL(seed_first_kernel, dim3(nb), dim3(64), 0, s, sl, b0, N, chain, chain_batch_stride);
-        for (int j = 1; j < k_max; ++j) {
+        if (j_begin == 0) hipLaunchKernelGGL(seed_first_kernel, dim3(nb), dim3(64), 0, s, sl, b0, N, chain, chain_batch_stride);
+        for (int j = j_begin > 1 ? j_begin : 1; j < k_max; ++j) {
             hipLaunchKernelGGL(seed_update_kernel, dim3(seed_blocks, nb), dim3(256), 0, s,
                                X + (int64_t)b0 * x_batch_stride, N, (int)d, ldx, x_batch_stride,
                                chain + (int64_t)b0 * chain_batch_stride, chain_batch_stride, j,

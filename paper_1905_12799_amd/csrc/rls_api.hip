@@ -213,6 +213,100 @@ int32_t rls_kmeans_sweep(const float *X_dev, int64_t N, int32_t d, int64_t ldx, 
                                     workspace_bytes, stream);
 }
 
+static int32_t until_knee_workspace(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t k_wave, int64_t *bytes)
+{
+    int64_t need = 0;
+    for (int32_t k_lo = k_min; k_lo <= k_max; k_lo += k_wave) {
+        const int32_t k_hi = k_lo + k_wave - 1 < k_max ? k_lo + k_wave - 1 : k_max;
+        SweepPlan plan;
+        const int32_t rc = make_sweep_plan(N, d, k_lo, k_hi, 1, &plan);
+        if (rc != RLS_OK) return rc;
+        SweepLayout L;
+        sweep_layout(plan, N, d, k_max, 1, &L);     // chain sized for k_max: the leading blocks sit at the same offsets in every wave
+        if (L.total > need) need = L.total;
+    }
+    *bytes = need;
+    return RLS_OK;
+}
+
+int64_t rls_kmeans_sweep_until_knee_workspace_bytes(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t k_wave)
+{
+    const int32_t rc = check_sweep(N, d, k_min, k_max, 1);
+    if (rc != RLS_OK) return rc;
+    if (k_wave < 1) return RLS_ERR_INVALID_ARG;
+    int64_t bytes = 0;
+    const int32_t wrc = until_knee_workspace(N, d, k_min, k_max, k_wave, &bytes);
+    return wrc != RLS_OK ? wrc : bytes;
+}
+
+int32_t rls_kmeans_sweep_until_knee(const float *X_dev, int64_t N, int32_t d, int64_t ldx, int32_t k_min, int32_t k_max,
+                                    int32_t k_wave, int32_t iters, uint64_t seed, const int64_t *init_idx_dev,
+                                    double knee_const, int32_t *labels_dev, float *centroids_dev, double *inertia_dev,
+                                    double *inertia_host, int32_t *k_out, int32_t *n_done_out, int32_t *status_dev,
+                                    void *workspace_dev, int64_t workspace_bytes, void *stream)
+{
+    int32_t rc = check_matrix(X_dev, N, d, ldx);
+    if (rc != RLS_OK) return rc;
+    rc = check_sweep(N, d, k_min, k_max, 1);
+    if (rc != RLS_OK) return rc;
+    if (!centroids_dev || !inertia_dev || !inertia_host || !k_out || !n_done_out || !status_dev) return RLS_ERR_NULL;
+    if (iters < 0 || k_wave < 1) return RLS_ERR_INVALID_ARG;
+    if (ldx > RLS_MAX_LDX) return RLS_ERR_SHAPE;
+    int64_t need = 0;
+    rc = until_knee_workspace(N, d, k_min, k_max, k_wave, &need);
+    if (rc != RLS_OK) return rc;
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < need) return RLS_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace_dev);
+    hipStream_t s = (hipStream_t)stream;
+
+    double previous_loss = INFINITY;
+    int32_t chosen = k_max, n_done = 0, chain_done = 0;
+    bool fired = false;
+    for (int32_t k_lo = k_min; k_lo <= k_max && !fired; k_lo += k_wave) {
+        const int32_t k_hi = k_lo + k_wave - 1 < k_max ? k_lo + k_wave - 1 : k_max;
+        SweepPlan plan;
+        rc = make_sweep_plan(N, d, k_lo, k_hi, 1, &plan);
+        if (rc != RLS_OK) return rc;
+        SweepLayout L;
+        sweep_layout(plan, N, d, k_max, 1, &L);
+        const int64_t *init = init_idx_dev;
+        if (!init) {
+            // the chain grows with the waves: centres chain_done .. k_hi-1 are drawn now, from the distance state of the earlier ones
+            int64_t *chain = reinterpret_cast<int64_t *>(ws + L.chain);
+            RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_hi, &seed, chain, k_max,
+                                          reinterpret_cast<double *>(ws + L.mind), 0, reinterpret_cast<double *>(ws + L.bsum), 0,
+                                          L.seed_blocks, s, chain_done));
+            chain_done = k_hi;
+            init = chain;
+        }
+        const int64_t row0 = rows_before(k_min, k_lo - k_min);
+        SweepArgs a;
+        a.X = X_dev; a.N = N; a.d = d; a.ldx = ldx; a.x_batch_stride = 0; a.batch = 1; a.iters = iters;
+        a.init_idx = init; a.init_batch_stride = k_max;
+        a.labels = labels_dev ? labels_dev + (int64_t)(k_lo - k_min) * N : nullptr;
+        a.centroids = centroids_dev + row0 * d;
+        a.inertia = inertia_dev + (k_lo - k_min);
+        a.trace = nullptr;
+        a.status = status_dev; a.ws = ws;
+        RLS_HIP_TRY(launch_sweep(plan, L, a, s));
+        int32_t status_host = 0;
+        RLS_HIP_TRY(hipMemcpyAsync(inertia_host + (k_lo - k_min), inertia_dev + (k_lo - k_min),
+                                   (size_t)(k_hi - k_lo + 1) * sizeof(double), hipMemcpyDeviceToHost, s));
+        RLS_HIP_TRY(hipMemcpyAsync(&status_host, status_dev, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        RLS_HIP_TRY(hipStreamSynchronize(s));
+        n_done = k_hi - k_min + 1;
+        if (status_host != 0) { chosen = 0; break; }      // the data broke a precondition: see status_dev
+        for (int32_t k = k_lo; k <= k_hi; ++k) {
+            const double loss = inertia_host[k - k_min];
+            if (knee_const * loss > previous_loss) { chosen = k; fired = true; break; }
+            previous_loss = loss;
+        }
+    }
+    *k_out = chosen;
+    *n_done_out = n_done;
+    return RLS_OK;
+}
+
 int32_t rls_pick_knee(const double *inertia_host, int32_t k_min, int32_t k_max, double knee_const, int32_t *k_out)
 {
     if (!inertia_host || !k_out) return RLS_ERR_NULL;

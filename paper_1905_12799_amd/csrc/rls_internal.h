@@ -126,7 +126,7 @@ hipError_t launch_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, cons
 hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
                              int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
                              double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,
-                             int32_t seed_blocks, hipStream_t s);
+                             int32_t seed_blocks, hipStream_t s, int32_t j_begin = 0);
 
 struct SweepArgs {
     const float *X;

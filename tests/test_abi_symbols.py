@@ -69,6 +69,8 @@ def test_host_side_argument_checks(library):
     assert L.rls_kmeans_sweep(fake, 1000, 8, 8, 1, 16, 5, seed, null, null, null, fake, null, fake, fake, 1 << 40, null) == -2
     out = ctypes.c_int32(0)
     assert L.rls_pick_knee(None, 1, 4, 1.05, ctypes.byref(out)) == -2
+    assert L.rls_kmeans_sweep_until_knee_workspace_bytes(1000, 8, 1, 16, 0) == -1      # k_wave < 1
+    assert 0 < L.rls_kmeans_sweep_until_knee_workspace_bytes(1000, 8, 1, 16, 8) <= wsb(1000, 8, 1, 16, 1) * 2
     d = binding._Domains(9, 4096, 4096)
     assert L.rls_snap_to_valid(fake, 4, 8, 8, ctypes.byref(d), fake, null) == -3   # more knobs than columns
     d8 = binding._Domains(8, 4096, 4096)

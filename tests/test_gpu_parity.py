@@ -354,6 +354,31 @@ def test_sweep_wide_columns(rls, orc):
     assert compare_sweep(orc, X, res, ref, 1, 9) == 0
 
 
+@pytest.mark.parametrize("name,N,k_min,k_max,k_wave,const", [
+    ("tiny", None, 1, 16, 8, 1.05), ("tiny", None, 1, 16, 3, 1.5), ("tiny", None, 2, 16, 5, 1.0001),
+    ("mid", 20000, 1, 40, 8, 1.05), ("mid", 20000, 8, 63, 16, 1.02), ("mid", 20000, 1, 24, 8, 1e9)])
+def test_sweep_until_knee_equals_full_sweep_and_oracle(rls, orc, name, N, k_min, k_max, k_wave, const):
+    """Algorithm 1's early exit: same chosen k and same outputs for the computed k as sweeping the whole range."""
+    w = synth.WORKLOADS[name]
+    p = synth.make_problem(w, N=N)
+    Xd = dev(p.X)
+    iters = 6
+    k_star, n_done, part = rls.kmeans_sweep_until_knee(Xd, k_min, k_max, k_wave, iters, const, seed=w.seed)
+    full = rls.kmeans_sweep(Xd, k_min, k_max, iters, seed=w.seed)
+    ref = orc.kmeans_sweep(p.X, k_min, k_max, iters, seed=w.seed)
+    assert k_star == orc.pick_knee(ref["inertia"], k_min, k_max, const)
+    assert k_star == rls.pick_knee(full.inertia.cpu().tolist(), k_min, k_max, const)
+    # a whole number of waves was computed, the last of them holds the chosen k (or everything was computed)
+    assert n_done >= k_star - k_min + 1
+    assert n_done == k_max - k_min + 1 or n_done % k_wave == 0
+    assert n_done <= ((k_star - k_min) // k_wave + 1) * k_wave
+    rows_done = sum(range(k_min, k_min + n_done))
+    np.testing.assert_array_equal(part.inertia[:n_done].cpu().numpy(), full.inertia[:n_done].cpu().numpy())
+    np.testing.assert_array_equal(part.centroids[:rows_done * w.d].cpu().numpy(), full.centroids[:rows_done * w.d].cpu().numpy())
+    np.testing.assert_array_equal(part.labels[:n_done].cpu().numpy(), full.labels[:n_done].cpu().numpy())
+    np.testing.assert_array_equal(part.labels[:n_done].cpu().numpy(), ref["labels"][:n_done])
+
+
 def test_sweep_status_flags(rls):
     X = np.ones((600, 8), dtype=np.float32)
     X[5, 2] = np.inf
