@@ -288,17 +288,6 @@ struct WaveCtx {
     float eps_a;
 };
 
-// squared distance restricted to the features [f0, f0 + nf) of a row pair, fp64 direct form
-__device__ inline double sqdist64_part(const float *x, const float *c, int nf)
-{
-    double acc = 0.0;
-    for (int l = 0; l < nf; ++l) {
-        const double diff = __dsub_rn((double)x[l], (double)c[l]);
-        acc = __dadd_rn(acc, __dmul_rn(diff, diff));
-    }
-    return acc;
-}
-
 template <int DP, int S, bool FINAL, bool TRACE>
 __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 {
@@ -370,6 +359,9 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         if (lane == 0) v = atomicAdd(c.next_slab, 1);
         return __builtin_amdgcn_readfirstlane(v);
     };
+    double jown[ST];                                 // loss sums of the runs this lane owns
+#pragma unroll
+    for (int st = 0; st < ST; ++st) jown[st] = 0.0;
     int cur = wave;
     if (cur >= n_slabs) return;
     fetch(c.chunk_begin + (int64_t)cur * SLAB);
@@ -730,30 +722,52 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
         }
         if (LOSS) {
-            // loss of this assignment: each half-wave sums its features in fp64, the pair adds up
+            // Loss of this assignment: every lane sums, for each (point, run) pair it owns, the exact squared distance
+            // to the assigned centroid over all features in rising order; the other half of the row comes from the
+            // partner lane by register swap.  Padded features are zero on both sides and add +0.
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb) {
                 const bool pvalid = base + pb * 32 + n < c.chunk_end;
-                for (int r = 0; r < c.n_runs; ++r) {
-                    const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
-                    int lab = 0;
+                float xf[DP];
 #pragma unroll
-                    for (int st = 0; st < ST; ++st)
-                        if (st == ost) lab = m1[pb][st] & 127;
-                    const int labo = xchg32(lab);
-                    if (hl != oh) lab = labo;
-                    double part = 0.0;
-                    if (pvalid) {
-                        const int lrow = r * c.k0 + r * (r - 1) / 2 + lab;
-                        part = sqdist64_part(xraw[pb], c.cs + lrow * CS + f0, nf);
+                for (int s = 0; s < H; ++s) {
+                    const float other = xchg32(xraw[pb][s]);
+                    xf[s] = hl ? other : xraw[pb][s];
+                    xf[H + s] = hl ? xraw[pb][s] : other;
+                }
+#pragma unroll
+                for (int st = 0; st < ST; ++st) {
+                    const int rl = S == 8 ? 0 : hl * ST + st;
+                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
+                    const int row = active ? rl * c.k0 + rl * (rl - 1) / 2 + (m1[pb][st] & 127) : 0;
+                    const float *crow = c.cs + row * CS;
+                    double dist = 0.0;
+#pragma unroll
+                    for (int l = 0; l < DP; l += 4) {
+                        const float4 cv = *reinterpret_cast<const float4 *>(crow + l);
+                        double diff = __dsub_rn((double)xf[l], (double)cv.x);
+                        dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xf[l + 1], (double)cv.y);
+                        dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xf[l + 2], (double)cv.z);
+                        dist = __dadd_rn(dist, __dmul_rn(diff, diff));
+                        diff = __dsub_rn((double)xf[l + 3], (double)cv.w);
+                        dist = __dadd_rn(dist, __dmul_rn(diff, diff));
                     }
-                    const double sum = __dadd_rn(part, xchg32(part));
-                    if (hl == 0) jloc[r] = __dadd_rn(jloc[r], sum);
+                    if (active) jown[st] = __dadd_rn(jown[st], dist);
                 }
             }
         }
         cur = nxt;
         nxt = nxt2;
+    }
+    if (LOSS) {
+        // hand the sums over by run: run r of the group is owned by half-wave r / ST (by the lower one when S = 8)
+#pragma unroll
+        for (int r = 0; r < 8 / S; ++r) {
+            const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
+            jloc[r] = hl == oh ? jown[ost] : 0.0;
+        }
     }
 }
 
