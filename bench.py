@@ -45,7 +45,7 @@ def main() -> int:
                     help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -183,6 +183,21 @@ def replace_visited(cfg, visited, mode_cfg) -> Tuple[np.ndarray, np.ndarray]:
     return cfg, replaced
 
 
+def apply_actions(cfg, action, offsets, values, want_features: bool = True):
+    """Configuration updater: cfg [m][n_knobs] domain indices + action in {-1, 0, +1} -> (new cfg, features or None)."""
+    cfg = np.ascontiguousarray(cfg, dtype=np.int32)
+    action = np.ascontiguousarray(action, dtype=np.int8)
+    m, n_knobs = cfg.shape
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    values = _f32(values)
+    out = np.empty_like(cfg)
+    feats = np.zeros((m, n_knobs), dtype=np.float32) if want_features else None
+    rc = lib().orc_apply_actions(_p(cfg), _p(action), ctypes.c_int64(m), ctypes.c_int32(n_knobs), _p(offsets), _p(values),
+                                 _p(out), _p(feats), ctypes.c_int64(n_knobs))
+    _check(rc, "apply_actions")
+    return out, feats
+
+
 def two_nearest(x, C) -> Tuple[float, float, int]:
     x = _f32(x)
     C = _f32(C)

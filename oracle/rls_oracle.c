@@ -382,6 +382,37 @@ int32_t orc_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, const int3
     return ORC_OK;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Configuration updater of the search agent (Sec. 4.1, "Action space" and    */
+/* "Learning procedure"): an action is one direction per dimension -         */
+/* decrement, stay or increment - and applying it to a configuration gives   */
+/* the next one.  Configurations are rows of domain indices; a step that     */
+/* would leave a knob's domain stays at its border (the paper is silent on   */
+/* the border).  features (optional, [m][ldf]) receives the domain values of */
+/* the new configurations in its first n_knobs columns, the form in which    */
+/* the cost model is queried.                                                 */
+int32_t orc_apply_actions(const int32_t *cfg, const int8_t *action, int64_t m, int32_t n_knobs, const int32_t *offsets,
+                          const float *values, int32_t *cfg_out, float *features, int64_t ldf)
+{
+    if (!cfg || !action || !offsets || !cfg_out || m < 1 || n_knobs < 1) return ORC_ERR_ARG;
+    if (features && (!values || ldf < n_knobs)) return ORC_ERR_ARG;
+    for (int64_t i = 0; i < m; ++i) {
+        for (int32_t j = 0; j < n_knobs; ++j) {
+            const int32_t size = offsets[j + 1] - offsets[j];
+            const int32_t a = action[i * n_knobs + j];
+            if (size < 1 || a < -1 || a > 1) return ORC_ERR_ARG;
+            int32_t v = cfg[i * n_knobs + j];
+            if (v < 0 || v >= size) return ORC_ERR_ARG;
+            v += a;
+            if (v < 0) v = 0;
+            if (v > size - 1) v = size - 1;
+            cfg_out[i * n_knobs + j] = v;
+            if (features) features[i * ldf + j] = values[offsets[j] + v];
+        }
+    }
+    return ORC_OK;
+}
+
 /* threads the annotated assignment loop runs on */
 int32_t orc_threads(void)
 {
