@@ -12,6 +12,7 @@
  *   rls_snap_to_valid   NextSamples = Centroids, as valid configurations
  *   rls_knob_modes      mode(s_Theta), dimension by dimension
  *   rls_replace_visited samples already in v_Theta give way to mode(s_Theta)
+ *   rls_apply_actions   the search agent's configuration updater (producer of the trajectory)
  *
  * Conventions
  *   - Plain C. Every call returns an int32_t status: RLS_OK or a negative RLS_ERR_* code.
@@ -231,6 +232,19 @@ int32_t rls_knob_modes(const float *X_dev, int64_t N, int32_t d, int64_t ldx, co
  */
 int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const int32_t *visited_dev,
                             int64_t n_visited, const int32_t *mode_cfg_dev, int32_t *replaced_dev, void *stream);
+
+/*
+ * Configuration updater of the search agent (Sec. 4.1, "Action space", "Learning procedure"): an action is one
+ * direction per dimension (-1 decrement, 0 stay, +1 increment); applying it to a configuration gives the next one
+ * of the trajectory.  A step that would leave a knob's domain stays at the border (the paper does not say).
+ *   cfg_dev      [m][n_knobs] int32 domain indices (values outside a domain are first brought to its border)
+ *   action_dev   [m][n_knobs] int8 (values beyond +-1 count as +-1)
+ *   cfg_out_dev  [m][n_knobs] int32 (written; may be cfg_dev)
+ *   features_dev [m][ldf] fp32 or null: the first n_knobs columns receive the domain values of the new
+ *                configurations, the form in which rls_gbt_score is queried for a whole trajectory
+ */
+int32_t rls_apply_actions(const int32_t *cfg_dev, const int8_t *action_dev, int64_t m, const rls_knob_domains *domains,
+                          int32_t *cfg_out_dev, float *features_dev, int64_t ldf, void *stream);
 
 /*
  * Timing aid for benchmarks (not part of the paper's method).  While enabled, rls_kmeans_sweep[_batched]

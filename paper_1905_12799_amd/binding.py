@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.rls_knob_modes.argtypes = [vp, i64, i32, i64, ctypes.POINTER(_Domains), i32, vp, vp, vp]
         L.rls_replace_visited.restype = i32
         L.rls_replace_visited.argtypes = [vp, i32, i32, vp, i64, vp, vp, vp]
+        L.rls_apply_actions.restype = i32
+        L.rls_apply_actions.argtypes = [vp, vp, i64, ctypes.POINTER(_Domains), vp, vp, i64, vp]
         L.rls_profile_enable.restype = i32
         L.rls_profile_enable.argtypes = [i32]
         L.rls_profile_read.restype = i32
@@ -373,6 +375,21 @@ def replace_visited(cfg: torch.Tensor, visited: Optional[torch.Tensor], mode_cfg
                                      _ptr(_dev(mode_cfg, torch.int32, "mode_cfg")), _ptr(replaced), _stream()),
            "rls_replace_visited")
     return replaced
+
+
+def apply_actions(cfg: torch.Tensor, action: torch.Tensor, domains: DeviceDomains, want_features: bool = True):
+    """Configuration updater: cfg int32 [m][n_knobs] + action int8 in {-1, 0, +1} -> (new cfg, features [m][n_knobs] or None)."""
+    _dev(cfg, torch.int32, "cfg")
+    _dev(action, torch.int8, "action")
+    m, n_knobs = cfg.shape
+    if not (cfg.is_contiguous() and action.is_contiguous()) or action.shape != cfg.shape or n_knobs != domains.n_knobs:
+        raise ValueError("cfg and action must be contiguous [m][n_knobs] with the domains' n_knobs")
+    out = torch.empty_like(cfg)
+    feats = torch.empty((m, n_knobs), dtype=torch.float32, device=cfg.device) if want_features else None
+    st = domains.struct()
+    _check(lib().rls_apply_actions(_ptr(cfg), _ptr(action), m, ctypes.byref(st), _ptr(out), _ptr(feats), n_knobs, _stream()),
+           "rls_apply_actions")
+    return out, feats
 
 
 def snap_to_valid_batched(centroids: torch.Tensor, domains: Sequence[DeviceDomains],

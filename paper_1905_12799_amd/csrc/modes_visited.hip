@@ -141,6 +141,26 @@ __global__ void visited_apply_kernel(int32_t *__restrict__ cfg, int k, int n_kno
     if (replaced[e / n_knobs]) cfg[e] = mode_cfg[e % n_knobs];
 }
 
+// Configuration updater of the search agent (Sec. 4.1 of the paper): one thread per (configuration, knob) adds the
+// direction to the domain index and holds it at the domain's borders; optionally writes the knob's value as feature.
+__global__ void apply_actions_kernel(const int32_t *__restrict__ cfg, const signed char *__restrict__ action, int64_t m,
+                                     DomainArgs dm, int32_t *__restrict__ cfg_out, float *__restrict__ features, int64_t ldf)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= m * dm.n_knobs) return;
+    const int64_t i = e / dm.n_knobs;
+    const int j = (int)(e % dm.n_knobs);
+    const int lo = dm.offsets[j], size = dm.offsets[j + 1] - lo;
+    int a = action[e];
+    a = a < -1 ? -1 : (a > 1 ? 1 : a);                 // directions only
+    int v = cfg[e];
+    v = v < 0 ? 0 : (v > size - 1 ? size - 1 : v);     // a configuration outside its domain is brought inside first
+    v += a;
+    v = v < 0 ? 0 : (v > size - 1 ? size - 1 : v);
+    cfg_out[e] = v;
+    if (features) features[i * ldf + j] = dm.values[lo + v];
+}
+
 }  // namespace
 
 hipError_t launch_knob_modes(const float *X, int64_t N, int64_t ldx, const DomainArgs &dm, int32_t n_total,
@@ -179,6 +199,15 @@ hipError_t launch_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, cons
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(visited_apply_kernel, dim3((k * n_knobs + 255) / 256), dim3(256), 0, s, cfg, (int)k, (int)n_knobs,
                        mode_cfg, replaced);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_actions(const int32_t *cfg, const signed char *action, int64_t m, const DomainArgs &dm,
+                                int32_t *cfg_out, float *features, int64_t ldf, hipStream_t s)
+{
+    const int64_t total = m * dm.n_knobs;
+    hipLaunchKernelGGL(apply_actions_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, cfg, action, m, dm, cfg_out,
+                       features, ldf);
     return hipGetLastError();
 }
 

@@ -370,4 +370,17 @@ int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const 
     return RLS_OK;
 }
 
+int32_t rls_apply_actions(const int32_t *cfg_dev, const int8_t *action_dev, int64_t m, const rls_knob_domains *domains,
+                          int32_t *cfg_out_dev, float *features_dev, int64_t ldf, void *stream)
+{
+    if (!cfg_dev || !action_dev || !domains || !cfg_out_dev) return RLS_ERR_NULL;
+    if (!domains->offsets_dev || !domains->values_dev) return RLS_ERR_NULL;
+    if (m < 1 || m > ((int64_t)1 << 31) || domains->n_knobs < 1 || domains->n_knobs > RLS_MAX_D) return RLS_ERR_INVALID_ARG;
+    if (features_dev && ldf < domains->n_knobs) return RLS_ERR_SHAPE;
+    const DomainArgs dm{domains->n_knobs, domains->offsets_dev, domains->values_dev};
+    RLS_HIP_TRY(launch_apply_actions(cfg_dev, reinterpret_cast<const signed char *>(action_dev), m, dm, cfg_out_dev,
+                                     features_dev, ldf, (hipStream_t)stream));
+    return RLS_OK;
+}
+
 }  // extern "C"

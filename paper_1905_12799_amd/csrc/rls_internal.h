@@ -123,6 +123,9 @@ hipError_t launch_knob_modes(const float *X, int64_t N, int64_t ldx, const Domai
 hipError_t launch_replace_visited(int32_t *cfg, int32_t k, int32_t n_knobs, const int32_t *visited, int64_t n_visited,
                                   const int32_t *mode_cfg, int32_t *replaced, hipStream_t s);
 
+hipError_t launch_apply_actions(const int32_t *cfg, const signed char *action, int64_t m, const DomainArgs &dm,
+                                int32_t *cfg_out, float *features, int64_t ldf, hipStream_t s);
+
 hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
                              int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
                              double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,

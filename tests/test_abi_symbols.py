@@ -81,6 +81,9 @@ def test_host_side_argument_checks(library):
     assert L.rls_replace_visited(fake, 4, 8, null, 10, fake, fake, null) == -2                  # visited rows missing
     assert L.rls_replace_visited(fake, 0, 8, fake, 10, fake, fake, null) == -1
     assert L.rls_replace_visited(fake, 4, 33, fake, 10, fake, fake, null) == -1
+    assert L.rls_apply_actions(fake, null, 10, ctypes.byref(d8), fake, null, 0, null) == -2
+    assert L.rls_apply_actions(fake, fake, 0, ctypes.byref(d8), fake, null, 0, null) == -1
+    assert L.rls_apply_actions(fake, fake, 10, ctypes.byref(d8), fake, fake, 4, null) == -3          # feature rows too short
 
 
 def test_pick_knee_matches_golden_cases(library):

@@ -169,6 +169,25 @@ def test_replace_visited_matches_oracle(rls, orc):
     np.testing.assert_array_equal(cfg_d.cpu().numpy(), cfg)
 
 
+def test_apply_actions_matches_oracle_and_feeds_scoring(rls, orc):
+    """Configuration updater: a trajectory of agent steps, every configuration equal to the oracle's, then scored."""
+    w = synth.WORKLOADS["tiny"]
+    p = synth.make_problem(w)
+    rng = np.random.default_rng(13)
+    sizes = np.diff(p.dom_offsets)
+    cfg = np.stack([rng.integers(0, s, size=4097) for s in sizes], axis=1).astype(np.int32)
+    dom = rls.DeviceDomains(p.dom_offsets, p.dom_values)
+    forest = rls.DeviceForest.from_host(p.forest)
+    cur_d, cur_h = dev(cfg), cfg
+    for step in range(4):
+        act = rng.integers(-1, 2, size=cfg.shape).astype(np.int8)
+        cur_d, feats_d = rls.apply_actions(cur_d, dev(act), dom)
+        cur_h, feats_h = orc.apply_actions(cur_h, act, p.dom_offsets, p.dom_values)
+        np.testing.assert_array_equal(cur_d.cpu().numpy(), cur_h)
+        np.testing.assert_array_equal(feats_d.cpu().numpy(), feats_h)
+        np.testing.assert_array_equal(rls.gbt_score(forest, feats_d).cpu().numpy(), orc.gbt_score(p.forest, feats_h)[0])
+
+
 # ----------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("name,N,k_max", [("tiny", None, 16), ("mid", 30000, 40), ("large", 5000, 24)])
 def test_seeding_chain(rls, orc, name, N, k_max):
