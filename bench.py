@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--workload", default="whole_layer", choices=["tiny", "mid", "whole_layer", "large", "batched"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
+    ap.add_argument("--no-early-exit", action="store_true", help="skip the extra timing of the sweep with early exit at the knee")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -194,7 +195,7 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    if not batched:
+    if not batched and not args.no_early_exit:
         # Algorithm 1 with its early exit at the knee (k in waves of 8), outside the timed steps: same chosen k,
         # only the waves up to the knee are computed
         k_e, n_done, _ = rls.kmeans_sweep_until_knee(X, w.k_min, w.k_max, 8, w.iters, knee_const, seed=seeds[0],
