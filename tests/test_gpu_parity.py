@@ -274,6 +274,10 @@ def test_sweep_trace_is_monotone(rls):
     (2000, 20, 30, 40, 2),    # d padded to 32, mid k only
     (500, 16, 1, 8, 0),       # no Lloyd round: assignment against the seeds only
     (128, 8, 128, 128, 2),    # k = N = the largest k
+    (1, 8, 1, 1, 2),          # a single point
+    (2, 3, 1, 2, 3),          # two points, k up to N
+    (33, 16, 1, 33, 2),       # one point past a 32-point block, k up to N
+    (64, 32, 60, 64, 1),      # exactly one slab at d = 32... and a second, k close to N
 ])
 def test_sweep_shapes(rls, orc, N, d, k_min, k_max, iters):
     rng = np.random.default_rng(N * 31 + d)
