@@ -207,6 +207,10 @@ def main() -> int:
         "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / args.steps,
                      "modes_visited": stage_ms["modes_visited"] / args.steps},
         "roofline": roofline,
+        # tree scoring: bound by LDS gathers and vector issue (T*D node visits per 4d+4 bytes), shown against HBM for scale
+        "gbt_score": {"ms": score_ms, "node_visits_per_s": float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3),
+                      "algorithmic_GBps": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9,
+                      "hbm_frac": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
 
     if not batched and not args.no_early_exit:
