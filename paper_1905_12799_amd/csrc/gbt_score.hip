@@ -3,8 +3,10 @@
 // One configuration per lane.  A workgroup keeps a tile of P configurations in LDS, feature-major
 // (xs[f][p]): the walk reads xs[feat][lane], whose bank is lane % 32 whatever `feat` is, so these
 // gathers never conflict.  The forest is streamed through LDS in chunks of whole trees with each
-// internal node packed as (feature, threshold bits); every lane adds the leaf values to its own fp32
-// running sum in tree order, which makes the result independent of the launch shape.
+// internal node packed as (LDS byte offset of the feature's row, threshold bits); every lane adds the leaf
+// values to its own fp32 running sum in tree order, which makes the result independent of the launch shape.
+// A step of the walk is two dependent LDS reads and four vector instructions: the walk keeps the node's LDS
+// address a (node n of a tree at byte b sits at b + 8 n) and moves to child 2n + 1 + c by a <- 2 a + (8 + 8 c - b).
 #include "rls_internal.h"
 
 namespace rls {
@@ -50,34 +52,38 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
         for (int e = tid; e < tc * n_int; e += P) {
             int ft = f.feat[(size_t)t0 * n_int + e];
             ft = min(max(ft, 0), d - 1);
-            nodes[e] = make_uint2((unsigned)ft, __float_as_uint(f.thr[(size_t)t0 * n_int + e]));
+            nodes[e] = make_uint2((unsigned)ft * (unsigned)P * 4u, __float_as_uint(f.thr[(size_t)t0 * n_int + e]));
         }
         for (int e = tid; e < tc * n_leaf; e += P) leaves[e] = f.leaf[(size_t)t0 * n_leaf + e];
         __syncthreads();
         // Four trees are walked side by side: a walk is a chain of dependent LDS reads (node, then feature value),
         // and independent chains keep more of them in flight.  The leaves are still added in tree order.
         constexpr int W = 4;
+        const unsigned nodes_at = (unsigned)((size_t)d * P * 4);        // byte offset of the node block in LDS
+        const unsigned tid4 = (unsigned)tid * 4u;
         for (int t = 0; t < tc; t += W) {
-            const uint2 *tn[W];
-            int n[W];
+            unsigned base[W], a[W], k_left[W], k_right[W];
 #pragma unroll
             for (int w = 0; w < W; ++w) {
-                tn[w] = nodes + (size_t)min(t + w, tc - 1) * n_int;
-                n[w] = 0;
+                base[w] = nodes_at + (unsigned)min(t + w, tc - 1) * (unsigned)n_int * 8u;
+                a[w] = base[w];
+                k_left[w] = 8u - base[w];      // x < threshold: child 2n + 1
+                k_right[w] = 16u - base[w];    // otherwise: child 2n + 2
+                asm volatile("" : "+v"(k_left[w]), "+v"(k_right[w]));   // keep both as they are: one select per step
             }
             for (int lev = 0; lev < f.depth; ++lev) {
                 uint2 nd[W];
 #pragma unroll
-                for (int w = 0; w < W; ++w) nd[w] = tn[w][n[w]];
+                for (int w = 0; w < W; ++w) nd[w] = *reinterpret_cast<const uint2 *>(smem + a[w]);
                 float xv[W];
 #pragma unroll
-                for (int w = 0; w < W; ++w) xv[w] = xs[nd[w].x * P + tid];
+                for (int w = 0; w < W; ++w) xv[w] = *reinterpret_cast<const float *>(smem + (nd[w].x + tid4));
 #pragma unroll
-                for (int w = 0; w < W; ++w) n[w] = 2 * n[w] + 1 + ((xv[w] < __uint_as_float(nd[w].y)) ? 0 : 1);
+                for (int w = 0; w < W; ++w) a[w] = 2u * a[w] + ((xv[w] < __uint_as_float(nd[w].y)) ? k_left[w] : k_right[w]);
             }
 #pragma unroll
             for (int w = 0; w < W; ++w)
-                if (t + w < tc) sum = sum + leaves[(t + w) * n_leaf + (n[w] - n_int)];
+                if (t + w < tc) sum = sum + leaves[(t + w) * n_leaf + (int)((a[w] - base[w]) >> 3) - n_int];
         }
     }
     if (valid) score[row] = sum;
