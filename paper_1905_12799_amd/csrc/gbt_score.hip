@@ -13,7 +13,7 @@ namespace rls {
 
 namespace {
 
-constexpr int kForestChunkBytes = 64 * 1024;
+constexpr int kForestChunkBytes = 96 * 1024;   // with the 64 KB tile of configurations this fills the 160 KB of LDS
 
 __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int64_t N, int d, int64_t ldx,
                                  float *__restrict__ score, int trees_per_chunk)
@@ -45,17 +45,45 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
         }
     }
 
+    // The next chunk of the forest travels in registers while the current one is walked: its loads are issued
+    // before the walk (unconditional, indices clamped) and written to LDS after it.  kStage entries per thread
+    // cover a chunk of kForestChunkBytes at 512 threads.
+    constexpr int kStage = (kForestChunkBytes / 12 + 511) / 512 + 1;
+    int st_feat[kStage];
+    float st_thr[kStage], st_leaf[kStage];
+    auto fetch_chunk = [&](int t0, int tc) {
+        const int n_nodes = tc * n_int, n_leaves = tc * n_leaf;
+#pragma unroll
+        for (int i = 0; i < kStage; ++i) {
+            const int e = tid + i * P;
+            const size_t en = (size_t)t0 * n_int + min(e, n_nodes - 1), el = (size_t)t0 * n_leaf + min(e, n_leaves - 1);
+            st_feat[i] = f.feat[en];
+            st_thr[i] = f.thr[en];
+            st_leaf[i] = f.leaf[el];
+        }
+    };
+    auto store_chunk = [&](int tc) {
+        const int n_nodes = tc * n_int, n_leaves = tc * n_leaf;
+#pragma unroll
+        for (int i = 0; i < kStage; ++i) {
+            const int e = tid + i * P;
+            if (e < n_nodes) {
+                const int ft = min(max(st_feat[i], 0), d - 1);
+                nodes[e] = make_uint2((unsigned)ft * (unsigned)P * 4u, __float_as_uint(st_thr[i]));
+            }
+            if (e < n_leaves) leaves[e] = st_leaf[i];
+        }
+    };
+
     float sum = f.base;
+    fetch_chunk(0, min(trees_per_chunk, f.n_trees));
+    store_chunk(min(trees_per_chunk, f.n_trees));
+    __syncthreads();   // first chunk and xs in place
     for (int t0 = 0; t0 < f.n_trees; t0 += trees_per_chunk) {
         const int tc = min(trees_per_chunk, f.n_trees - t0);
-        __syncthreads();   // previous chunk fully consumed (and, first time, xs written)
-        for (int e = tid; e < tc * n_int; e += P) {
-            int ft = f.feat[(size_t)t0 * n_int + e];
-            ft = min(max(ft, 0), d - 1);
-            nodes[e] = make_uint2((unsigned)ft * (unsigned)P * 4u, __float_as_uint(f.thr[(size_t)t0 * n_int + e]));
-        }
-        for (int e = tid; e < tc * n_leaf; e += P) leaves[e] = f.leaf[(size_t)t0 * n_leaf + e];
-        __syncthreads();
+        const int t_next = t0 + trees_per_chunk;
+        const int tc_next = min(trees_per_chunk, f.n_trees - t_next);
+        if (tc_next > 0) fetch_chunk(t_next, tc_next);
         // Four trees are walked side by side: a walk is a chain of dependent LDS reads (node, then feature value),
         // and independent chains keep more of them in flight.  The leaves are still added in tree order.
         constexpr int W = 4;
@@ -85,6 +113,9 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
             for (int w = 0; w < W; ++w)
                 if (t + w < tc) sum = sum + leaves[(t + w) * n_leaf + (int)((a[w] - base[w]) >> 3) - n_int];
         }
+        __syncthreads();   // every wave is done with this chunk
+        if (tc_next > 0) store_chunk(tc_next);
+        __syncthreads();
     }
     if (valid) score[row] = sum;
 }
