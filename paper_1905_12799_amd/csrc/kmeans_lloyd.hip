@@ -1351,6 +1351,8 @@ int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows)
     return carve_lds(dp, d, n_tiles, real_rows).total;
 }
 
+constexpr int kFillWorkgroups = 256;   // one per compute unit
+
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch, SweepPlan *plan)
 {
     const int dp = padded_d(d);
@@ -1404,6 +1406,12 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
     const int64_t tiles_total = (N + tp - 1) / tp;
     const int64_t units = (int64_t)plan->n_groups * (batch > 0 ? batch : 1);
     int64_t want = (1024 + units - 1) / units;
+    // a workgroup should have several slabs per wave to spread its set-up over: at least 4096 points per chunk
+    // but never fewer workgroups than fill the chip
+    int64_t most = (N + 4095) / 4096;
+    const int64_t fill = (kFillWorkgroups + units - 1) / units;
+    if (most < fill) most = fill;
+    if (want > most) want = most;
     if (want > tiles_total) want = tiles_total;
     if (want < 1) want = 1;
     int64_t chunk_len = ((tiles_total + want - 1) / want) * tp;

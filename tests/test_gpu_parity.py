@@ -396,7 +396,9 @@ def test_sweep_until_knee_equals_full_sweep_and_oracle(rls, orc, name, N, k_min,
     assert n_done == k_max - k_min + 1 or n_done % k_wave == 0
     assert n_done <= ((k_star - k_min) // k_wave + 1) * k_wave
     rows_done = sum(range(k_min, k_min + n_done))
-    np.testing.assert_array_equal(part.inertia[:n_done].cpu().numpy(), full.inertia[:n_done].cpu().numpy())
+    # the loss is a floating-point sum over chunks of points, and the chunking depends on how many k share a launch;
+    # centroids come from integer sums and labels from exact comparisons, so they are identical
+    np.testing.assert_allclose(part.inertia[:n_done].cpu().numpy(), full.inertia[:n_done].cpu().numpy(), rtol=1e-12)
     np.testing.assert_array_equal(part.centroids[:rows_done * w.d].cpu().numpy(), full.centroids[:rows_done * w.d].cpu().numpy())
     np.testing.assert_array_equal(part.labels[:n_done].cpu().numpy(), full.labels[:n_done].cpu().numpy())
     np.testing.assert_array_equal(part.labels[:n_done].cpu().numpy(), ref["labels"][:n_done])
