@@ -377,7 +377,6 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
             for (int s = 0; s < HP; ++s) xraw[pb][s] = (s < H && s < nf && pvalid) ? xnext[pb][s] : 0.0f;
         }
-        if (nxt < n_slabs) fetch(c.chunk_begin + (int64_t)nxt * SLAB);
         const int nxt2 = grab();
 
         // ---- B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
@@ -421,6 +420,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 oldl[pb][st] = FINAL ? 0xff : (int)prev_slab[poff[pb][st]];
             }
         }
+
+        // The rows of the next slab are asked for after this slab's previous labels (older requests complete first:
+        // waiting for the labels then does not wait for the rows) and are only needed when the next slab starts, a
+        // whole slab of work away.  Always issued - for the last slab it re-reads that slab - so that the number
+        // of requests in flight is the same on every path.
+        fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
 
         // ---- distances tile by tile; the results of one block are folded while the matrix pipeline runs the next
         // (the tile loop is written out twice so that the operand buffers and accumulators alternate by name
@@ -485,9 +490,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
         }
         fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
-        // the next rows have arrived by now; asking for them here, before this step's stores are issued,
-        // keeps the (in-order) memory counter from tying the next step to those stores
-        settle();
+        // the previous labels have arrived by now (the rows of the next slab may still be on their way)
         if (!FINAL) {
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb)
@@ -617,21 +620,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
         }
 
-        // labels are final: output, and which pairs moved
+        // labels are final: which pairs moved (the stores wait until the end of the slab)
         unsigned mv = 0;
+        if (!FINAL) {
 #pragma unroll
-        for (int pb = 0; pb < NB; ++pb) {
-            const int64_t p = base + pb * 32 + n;
+            for (int pb = 0; pb < NB; ++pb) {
+                const int64_t p = base + pb * 32 + n;
 #pragma unroll
-            for (int st = 0; st < ST; ++st) {
-                const int rl = S == 8 ? 0 : hl * ST + st;
-                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
-                const int lab = m1[pb][st] & 127;
-                if (FINAL) {
-                    if (active && c.labels_out) (c.labels_out + base)[poff[pb][st]] = lab;
-                } else {
-                    const bool moved = active && lab != oldl[pb][st];
-                    if (moved) prev_slab[poff[pb][st]] = (unsigned char)lab;
+                for (int st = 0; st < ST; ++st) {
+                    const int rl = S == 8 ? 0 : hl * ST + st;
+                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
+                    const bool moved = active && (m1[pb][st] & 127) != oldl[pb][st];
                     mv |= (unsigned)moved << (pb * ST + st);
                 }
             }
@@ -755,6 +754,24 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                         dist = __dadd_rn(dist, __dmul_rn(diff, diff));
                     }
                     if (active) jown[st] = __dadd_rn(jown[st], dist);
+                }
+            }
+        }
+        // The rows of the next slab have to be there now.  Asking here, before this slab's stores are issued, keeps
+        // the in-order memory counter from tying the next slab to those stores.
+        settle();
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb) {
+            const int64_t p = base + pb * 32 + n;
+#pragma unroll
+            for (int st = 0; st < ST; ++st) {
+                const int rl = S == 8 ? 0 : hl * ST + st;
+                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
+                const int lab = m1[pb][st] & 127;
+                if (FINAL) {
+                    if (active && c.labels_out) (c.labels_out + base)[poff[pb][st]] = lab;
+                } else {
+                    if ((mv >> (pb * ST + st)) & 1u) prev_slab[poff[pb][st]] = (unsigned char)lab;
                 }
             }
         }
