@@ -324,6 +324,14 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     unsigned foff[H];                                // this lane's clamped feature offsets (fixed for the launch)
 #pragma unroll
     for (int s = 0; s < H; ++s) foff[s] = (unsigned)(c.vec_x ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1));
+    int oldn[NB][ST];                                // previous labels of the slab being fetched
+    unsigned run_off[ST];                            // offset of this lane's runs in the label arrays (runs are N apart)
+#pragma unroll
+    for (int st = 0; st < ST; ++st) {
+        const unsigned rl = S == 8 ? 0u : (unsigned)(hl * ST + st);
+        run_off[st] = min(rl, (unsigned)(c.n_runs - 1)) * (unsigned)c.N;
+        for (int pb = 0; pb < NB; ++pb) oldn[pb][st] = 0xff;
+    }
     auto fetch = [&](int64_t slab_base) {
         const float *Xs = c.X + slab_base * c.ldx;
         const unsigned last = (unsigned)min((int64_t)(SLAB_ - 1), c.chunk_end - 1 - slab_base);
@@ -341,6 +349,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int s = 0; s < H; ++s) xnext[pb][s] = Xs[ro + foff[s]];
             }
+            // labels these (point, run) pairs had in the previous round, 0xff before the first one
+            if (!FINAL) {
+                const unsigned char *prev_slab = c.prev + slab_base;
+#pragma unroll
+                for (int st = 0; st < ST; ++st) oldn[pb][st] = (int)prev_slab[run_off[st] + li];
+            }
         }
     };
     // the outstanding loads of fetch() have to be complete here
@@ -349,6 +363,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
             for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xnext[pb][s]));
+        if (!FINAL) {
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int st = 0; st < ST; ++st) asm volatile("" : "+v"(oldn[pb][st]));
+        }
     };
     // The chunk is handed out in slabs of SLAB points: the first eight statically, the rest from a counter in
     // LDS, so the waves of the workgroup finish together however their close calls and updates are spread.
@@ -385,9 +405,6 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         float xn[NB];
         int m1[NB][ST], m2[NB][ST], m3[NB][ST];
         int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
-        unsigned poff[NB][ST];            // offset of the pair's label behind the slab's first point (runs are N apart)
-        unsigned char *prev_slab = c.prev + base;
-        const unsigned slab_last = (unsigned)min((int64_t)(SLAB - 1), c.chunk_end - 1 - base);
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             float xc[HP];
@@ -410,19 +427,14 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             unsigned nh, nm, nl;
             split3(xn[pb], nh, nm, nl);
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
-            // labels these (point, run) pairs had in the previous round, 0xff before the first one (the loads
-            // complete during the tile loop); same addressing: uniform base of the slab, 32-bit lane offset
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; m3[pb][st] = kBigKey;
-                const unsigned rl = S == 8 ? 0u : (unsigned)(hl * ST + st);
-                poff[pb][st] = min(rl, (unsigned)(c.n_runs - 1)) * (unsigned)c.N + min((unsigned)(pb * 32 + n), slab_last);
-                oldl[pb][st] = FINAL ? 0xff : (int)prev_slab[poff[pb][st]];
+                oldl[pb][st] = oldn[pb][st];        // fetched with the rows, a slab ago
             }
         }
 
-        // The rows of the next slab are asked for after this slab's previous labels (older requests complete first:
-        // waiting for the labels then does not wait for the rows) and are only needed when the next slab starts, a
+        // The rows and previous labels of the next slab are asked for now and only needed when that slab starts, a
         // whole slab of work away.  Always issued - for the last slab it re-reads that slab - so that the number
         // of requests in flight is the same on every path.
         fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
@@ -490,13 +502,6 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
         }
         fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
-        // the previous labels have arrived by now (the rows of the next slab may still be on their way)
-        if (!FINAL) {
-#pragma unroll
-            for (int pb = 0; pb < NB; ++pb)
-#pragma unroll
-                for (int st = 0; st < ST; ++st) asm volatile("" : "+v"(oldl[pb][st]));
-        }
 
         // ---- labels, close calls, sums
         constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
@@ -768,10 +773,11 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const int rl = S == 8 ? 0 : hl * ST + st;
                 const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
                 const int lab = m1[pb][st] & 127;
+                const unsigned off = run_off[st] + (unsigned)(pb * 32 + n);      // used for active pairs only: inside the chunk
                 if (FINAL) {
-                    if (active && c.labels_out) (c.labels_out + base)[poff[pb][st]] = lab;
+                    if (active && c.labels_out) (c.labels_out + base)[off] = lab;
                 } else {
-                    if ((mv >> (pb * ST + st)) & 1u) prev_slab[poff[pb][st]] = (unsigned char)lab;
+                    if ((mv >> (pb * ST + st)) & 1u) (c.prev + base)[off] = (unsigned char)lab;
                 }
             }
         }
