@@ -29,7 +29,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix
 # FETCH_SIZE / WRITE_SIZE in KiB per dispatch and the factors a plain 1 GiB copy gives for each counter.  Valid
 # only for the library version the counters were taken with; any other version reports traffic = null.
 HBM_COUNTERS = {
-    "whole_layer": {"version": 101, "fetch_kib": 330503.7, "write_kib": 54345.2, "fetch_scale": 2.0, "write_scale": 1.0},
+    "whole_layer": {"version": 102, "fetch_kib": 330433.3, "write_kib": 55462.7, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 
