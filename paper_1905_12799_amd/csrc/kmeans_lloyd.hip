@@ -38,6 +38,9 @@ constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by t
 constexpr int kLowBits = 36;                  // further bits kept by the low accumulator (wide columns)
 
 __host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 256 : 512; }
+// 32-point blocks a wave takes per slab: two, except at d_pad = 32 with many runs side by side, where the best keys
+// of 4 runs x 2 blocks would not fit the registers next to the operands
+__host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp == 32 && s < 4 ? 1 : 2; }
 // MFMA operands: a lane holds 8 bf16 values of its half of the features per K-step (v_mfma_f32_32x32x16_bf16);
 // a 32-row tile stores, per K-step, the three pieces (high, middle, low) of -2c', and then one bias slot.
 __host__ __device__ constexpr int ksteps_of(int dp) { return dp == 32 ? 2 : 1; }
@@ -291,8 +294,10 @@ struct WaveCtx {
 template <int DP, int S, bool FINAL, bool TRACE>
 __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 {
-    constexpr int TP = tile_points_of(DP);          // points per workgroup step
-    constexpr int NB = TP / (32 * kWaves);          // blocks of 32 points per wave and step
+    constexpr int NB = slab_blocks_of(DP, S);       // blocks of 32 points per wave and slab
+    // with 2 blocks at d_pad = 32 the rows of the next slab are requested after the tile loop, when the operand
+    // registers are free again, instead of before it
+    constexpr bool LATE_FETCH = DP == 32 && NB == 2;
     constexpr int H = DP / 2;                       // features per half-wave
     constexpr int CS = DP + 4;                      // row stride of the LDS copy of the centroids
     constexpr int NK = ksteps_of(DP);               // K-steps of 16 per cross term
@@ -437,7 +442,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         // The rows and previous labels of the next slab are asked for now and only needed when that slab starts, a
         // whole slab of work away.  Always issued - for the last slab it re-reads that slab - so that the number
         // of requests in flight is the same on every path.
-        fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
+        if (!LATE_FETCH) fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
 
         // ---- distances tile by tile; the results of one block are folded while the matrix pipeline runs the next
         // (the tile loop is written out twice so that the operand buffers and accumulators alternate by name
@@ -502,6 +507,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
         }
         fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+        if (LATE_FETCH) fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
 
         // ---- labels, close calls, sums
         constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
