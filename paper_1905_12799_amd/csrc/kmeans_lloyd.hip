@@ -126,37 +126,63 @@ __device__ inline double xchg32(double v)
     return __hiloint2double(hi, lo);
 }
 
-// half of a centroid row (the features of one half-wave) from the zero-padded LDS copy into registers
-template <int H>
-__device__ inline void load_half_row(float (&dst)[H], const float *src)
+// Minimum over the wave, in every lane, without a trip through LDS: lane exchanges inside rows of 16 by DPP (swap
+// neighbours, swap pairs, mirror halves of 8, mirror the row: after each step twice as many lanes agree), then
+// between rows with the two row-swap instructions.
+template <int CTRL>
+__device__ inline int dpp_move(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }   // every lane has a source
+template <int CTRL>
+__device__ inline double dpp_move(double v)
 {
-#pragma unroll
-    for (int l = 0; l < H; l += 4) {
-        const float4 v = *reinterpret_cast<const float4 *>(src + l);
-        dst[l] = v.x; dst[l + 1] = v.y; dst[l + 2] = v.z; dst[l + 3] = v.w;
+    return __hiloint2double(dpp_move<CTRL>(__double2hiint(v)), dpp_move<CTRL>(__double2loint(v)));
+}
+constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+__device__ inline double wave_min_f64(double v)
+{
+    v = fmin(v, dpp_move<kDppSwap1>(v));
+    v = fmin(v, dpp_move<kDppSwap2>(v));
+    v = fmin(v, dpp_move<kDppHalfMirror>(v));
+    v = fmin(v, dpp_move<kDppMirror>(v));
+    {
+        const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        v = fmin(__hiloint2double((int)rh[0], (int)rl[0]), __hiloint2double((int)rh[1], (int)rl[1]));   // own row, other row
     }
+    {
+        const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+        const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        v = fmin(__hiloint2double((int)rh[0], (int)rl[0]), __hiloint2double((int)rh[1], (int)rl[1]));
+    }
+    return v;
+}
+__device__ inline int wave_min_i32(int v)
+{
+    v = min(v, dpp_move<kDppSwap1>(v));
+    v = min(v, dpp_move<kDppSwap2>(v));
+    v = min(v, dpp_move<kDppHalfMirror>(v));
+    v = min(v, dpp_move<kDppMirror>(v));
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        v = min((int)r[0], (int)r[1]);
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        v = min((int)r[0], (int)r[1]);
+    }
+    return v;
 }
 
 // The assignment as it is defined, by one whole wave: fp64 direct-form distances sum_l (x_l - c_l)^2, features in
 // rising order, of one point to the k centroids of a run (one or two per lane), then the lexicographic minimum of
-// (distance, index) over the wave.  Every lane returns the winner.  The centroid rows come from the LDS copy,
-// which is zero beyond the last feature, as is the register copy of the point: padded terms add +0.
+// (distance, index) over the wave.  Every lane returns the winner.  The point arrives as wave-uniform values (read
+// out of the registers of the two lanes that hold its halves); the centroid rows come from the LDS copy, which is
+// zero beyond the last feature, as is the register copy of the point: padded terms add +0.
 template <int DP>
-__device__ inline int exact_argmin_wave(const float *xrow, const float *crun, int cstride, int k, int d, bool vec_x)
+__device__ inline int exact_argmin_wave(const float (&x)[DP], const float *crun, int cstride, int k)
 {
     const int lane = threadIdx.x & 63;
-    float x[DP];
-    if (vec_x) {
-#pragma unroll
-        for (int l = 0; l < DP; l += 4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (l < d) v = *reinterpret_cast<const float4 *>(xrow + l);
-            x[l] = v.x; x[l + 1] = v.y; x[l + 2] = v.z; x[l + 3] = v.w;
-        }
-    } else {
-#pragma unroll
-        for (int l = 0; l < DP; ++l) x[l] = l < d ? xrow[l] : 0.0f;
-    }
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int j = lane; j < k; j += 64) {
@@ -176,13 +202,12 @@ __device__ inline int exact_argmin_wave(const float *xrow, const float *crun, in
         }
         if (dist < best) { best = dist; arg = j; }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const double ob = __shfl_xor(best, off, 64);
-        const int oa = __shfl_xor(arg, off, 64);
-        if (ob < best || (ob == best && oa < arg)) { best = ob; arg = oa; }
-    }
-    return arg;
+    // smallest distance of the wave, then the smallest index among the lanes that hold it
+    const double wbest = wave_min_f64(best);
+    const unsigned long long tied = __ballot(best == wbest);
+    // up to 64 centroids a lane's index is its number: the first lane that holds the minimum has the smallest index
+    if (k <= 64) return __ffsll((long long)tied) - 1;
+    return wave_min_i32(best == wbest ? arg : 0x7fffffff);
 }
 
 // v = h + m + l exactly, each piece a bf16 (8 significant bits): h and m by truncation, l is what is left
@@ -244,24 +269,23 @@ __device__ inline int pack_key(float v, int mask, int idx)
 // median of three; the compiler selects the single med3 instruction for this shape
 __device__ inline int med3i(int a, int b, int c) { return max(min(a, b), min(max(a, b), c)); }
 
-// insert a key into the ascending triple (m1, m2, m3) of the smallest keys seen so far
-__device__ inline void insert3(int key, int &m1, int &m2, int &m3)
+// insert a key into the ascending pair (m1, m2) of the smallest keys seen so far
+__device__ inline void insert2(int key, int &m1, int &m2)
 {
-    m3 = med3i(m2, m3, key);      // third smallest of {m1, m2, m3, key} given m1 <= m2 <= m3
-    m2 = med3i(m1, m2, key);      // second smallest
+    m2 = med3i(m1, m2, key);      // second smallest of {m1, m2, key} given m1 <= m2
     m1 = min(m1, key);
 }
 
-// fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run states: the three smallest keys.
-// The third one only serves to show that a close call is between two candidates and no more.
+// fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run states: the two smallest keys
+// (three vector instructions per distance: and-or, med3, min).  The second one shows whether the first is a clear winner.
 template <int S, int ST>
-__device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST], int (&m3)[ST])
+__device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST])
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int st = state_of<S>(q);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) insert3(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), m1[st], m2[st], m3[st]);
+        for (int i = 0; i < 4; ++i) insert2(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), m1[st], m2[st]);
     }
 }
 
@@ -306,7 +330,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);   // runs owned by a lane
     constexpr int SLAB_ = 32 * NB;                  // points a wave takes at a time
     constexpr int NM = 6 * NK + 1;                  // MFMAs per tile block
-    constexpr int VPER = (64 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
+    constexpr int VPER = (48 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
     constexpr bool LOSS = FINAL || TRACE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hl = lane >> 5;
@@ -384,6 +408,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         if (lane == 0) v = atomicAdd(c.next_slab, 1);
         return __builtin_amdgcn_readfirstlane(v);
     };
+    // part of the error bound that belongs to a run (the centroids' largest squared norm), per run this lane owns
+    float tol_run[ST];
+#pragma unroll
+    for (int st = 0; st < ST; ++st) tol_run[st] = c.eps_a * c.cnmax_s[S == 8 ? 0 : hl * ST + st] + 1.0e-30f;
     double jown[ST];                                 // loss sums of the runs this lane owns
 #pragma unroll
     for (int st = 0; st < ST; ++st) jown[st] = 0.0;
@@ -395,12 +423,20 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 
     while (cur < n_slabs) {
         const int64_t base = c.chunk_begin + (int64_t)cur * SLAB;     // first point of this wave's slab
+        // (a lane past the end of the chunk holds a copy of the chunk's last row: its pairs are never active)
         float xraw[NB][HP];
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const bool pvalid = base + pb * 32 + n < c.chunk_end;
 #pragma unroll
-            for (int s = 0; s < HP; ++s) xraw[pb][s] = (s < H && s < nf && pvalid) ? xnext[pb][s] : 0.0f;
+            for (int s = 0; s < HP; ++s) xraw[pb][s] = s < H ? xnext[pb][s] : 0.0f;
+        }
+        if (d < DP) {
+            // padded features: the clamped loads brought real values of other features, they count as zero
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int s = 0; s < H; ++s)
+                    if (s >= nf) xraw[pb][s] = 0.0f;
         }
         const int nxt2 = grab();
 
@@ -408,7 +444,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
         bf16x8 bx[NB][3][NK], bb[NB];
         float xn[NB];
-        int m1[NB][ST], m2[NB][ST], m3[NB][ST];
+        int m1[NB][ST], m2[NB][ST];
         int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
@@ -434,7 +470,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
-                m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; m3[pb][st] = kBigKey;
+                m1[pb][st] = kBigKey; m2[pb][st] = kBigKey;
                 oldl[pb][st] = oldn[pb][st];        // fetched with the rows, a slab ago
             }
         }
@@ -483,9 +519,9 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
                 if (pb == 0) {
-                    if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+                    if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
                 } else {
-                    fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1], m3[pb - 1]);
+                    fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1]);
                 }
 #pragma unroll
                 for (int s = 0; s < NM; ++s) {
@@ -506,128 +542,70 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
             if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
         }
-        fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1], m3[NB - 1]);
+        fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
         if (LATE_FETCH) fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
 
         // ---- labels, close calls, sums
         constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
-        // Keys: which pairs does the exact arithmetic have to confirm?  pend2: against one rival (the third key
-        // is clear of the error bound), pend3: against the whole run.  Bit pb * ST + st of a lane's mask.
-        unsigned pend2 = 0, pend3 = 0;
+        // Keys: which pairs does the exact arithmetic have to confirm?  Bit pb * ST + st of a lane's mask.
+        unsigned pend = 0;
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             const bool pvalid = base + pb * 32 + n < c.chunk_end;
             if (S == 8) {
                 // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
-                int k1 = m1[pb][0], k2 = m2[pb][0], k3 = m3[pb][0];
+                int k1 = m1[pb][0], k2 = m2[pb][0];
                 if (k1 < kBigKey) k1 |= hl << 4;
                 if (k2 < kBigKey) k2 |= hl << 4;
-                if (k3 < kBigKey) k3 |= hl << 4;
-                const int o1 = xchg32(k1), o2 = xchg32(k2), o3 = xchg32(k3);
-                insert3(o1, k1, k2, k3);
-                insert3(o2, k1, k2, k3);
-                insert3(o3, k1, k2, k3);
-                m1[pb][0] = k1; m2[pb][0] = k2; m3[pb][0] = k3;
+                const int o1 = xchg32(k1), o2 = xchg32(k2);
+                insert2(o1, k1, k2);
+                insert2(o2, k1, k2);
+                m1[pb][0] = k1; m2[pb][0] = k2;
             }
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
                 const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
-                const int k1 = m1[pb][st], k2 = m2[pb][st], k3 = m3[pb][st];
+                const int k1 = m1[pb][st], k2 = m2[pb][st];
                 const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
-                const float f3 = __int_as_float(k3 & (int)0xffffff80);
                 // error bound of the two expansions (rounding of norms, products and the centring) plus the 7
                 // mantissa bits given up to the index: a key is its value cut down by less than 2^-16 of itself,
                 // so the smaller key's value may lie that much higher (2^-15 here)
-                const float tol0 = c.eps_a * (xn[pb] + c.cnmax_s[rl]) + 1.0e-30f;
-                const bool close = active && !(f2 - f1 > tol0 + 3.0517578125e-5f * fabsf(f2));
-                const bool clear3 = f3 - f1 > tol0 + 3.0517578125e-5f * fabsf(f3);
-                pend2 |= (unsigned)(close && clear3) << (pb * ST + st);
-                pend3 |= (unsigned)(close && !clear3) << (pb * ST + st);
+                const float tol0 = fmaf(c.eps_a, xn[pb], tol_run[st]);
+                const bool close = active && !(f2 - f1 > fmaf(3.0517578125e-5f, fabsf(f2), tol0));
+                pend |= (unsigned)close << (pb * ST + st);
             }
         }
 
-        // A close call between exactly two centroids is decided by the lane pair of the point with the exact
-        // arithmetic: the lower half-wave sums its features in fp64, the upper one continues the same sum with
-        // its features - the order of the plain loop over all features - and compares.  One pair per pass.
+        // A close call (about one pair in a thousand on knob data; every pair where centroids coincide or integer
+        // data ties exactly) is settled by the whole wave with the exact arithmetic over the run.  The point's row is
+        // read out of the registers of the two lanes that hold its halves.
         {
-            const unsigned other2 = xchg32(pend2);
-            unsigned both = hl ? (other2 | (pend2 << NBST)) : (pend2 | (other2 << NBST));
-            while (__ballot(both != 0u) != 0ull) {
-                const bool act = both != 0u;
-                const int bit = act ? __ffs(both) - 1 : 0;
-                both &= both - 1u;
-                const int oh = bit / NBST, idx = bit % NBST, pb = idx / ST, st = idx % ST;
-                int kk = 0;                         // the owner's two candidates
-#pragma unroll
-                for (int i = 0; i < NBST; ++i)
-                    if (i == idx) kk = (m1[i / ST][i % ST] & 127) | ((m2[i / ST][i % ST] & 127) << 8);
-                const int kko = xchg32(kk);
-                if (hl != oh) kk = kko;
-                const int j1 = kk & 0xff, j2 = kk >> 8;
-                const int rl = S == 8 ? 0 : oh * ST + st;
-                const float *crun = c.cs + (rl * c.k0 + rl * (rl - 1) / 2) * CS + f0;
-                float xs[H];
-#pragma unroll
-                for (int s = 0; s < H; ++s) {
-                    xs[s] = xraw[0][s];
-#pragma unroll
-                    for (int q = 1; q < NB; ++q)
-                        if (pb == q) xs[s] = xraw[q][s];
-                }
-                float c1[H], c2[H];
-                load_half_row<H>(c1, crun + j1 * CS);
-                load_half_row<H>(c2, crun + j2 * CS);
-                // the squared differences do not depend on the running sum: both half-waves form theirs at once,
-                // then the lower half adds its own up, hands the sum over, and the upper half goes on with it
-                double t1[H], t2[H];
-#pragma unroll
-                for (int l = 0; l < H; ++l) {
-                    const double e1 = __dsub_rn((double)xs[l], (double)c1[l]), e2 = __dsub_rn((double)xs[l], (double)c2[l]);
-                    t1[l] = __dmul_rn(e1, e1);
-                    t2[l] = __dmul_rn(e2, e2);
-                }
-                double d1 = 0.0, d2 = 0.0;
-                // (terms past the last feature are +0 and leave a sum as it is)
-                if (hl == 0) {
-#pragma unroll
-                    for (int l = 0; l < H; ++l) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
-                }
-                d1 = xchg32(d1);
-                d2 = xchg32(d2);
-                int win = j1;
-                if (hl == 1) {
-#pragma unroll
-                    for (int l = 0; l < H; ++l) { d1 = __dadd_rn(d1, t1[l]); d2 = __dadd_rn(d2, t2[l]); }
-                    win = (d2 < d1 || (d2 == d1 && j2 < j1)) ? j2 : j1;
-                }
-                const int wino = xchg32(win);
-                if (hl == 0) win = wino;
-                if (act && hl == oh) {
-#pragma unroll
-                    for (int i = 0; i < NBST; ++i)
-                        if (i == idx) m1[i / ST][i % ST] = win;
-                }
-            }
-        }
-        // Three or more candidates (exact ties on integer data, duplicate centroids): the whole wave scans the run.
-        {
-            unsigned long long todo = __ballot(pend3 != 0u);
+            unsigned long long todo = __ballot(pend != 0u);
             while (todo) {
                 const int src = __ffsll((long long)todo) - 1;
-                const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend3, src);
+                const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend, src);
                 const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
-                const int64_t sp = base + pb * 32 + (src & 31);
                 const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
                 const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * CS;
-                const int arg = exact_argmin_wave<DP>(c.X + sp * c.ldx, crun, CS, c.k0 + srl, d, c.vec_x);
+                float xs[DP];
+#pragma unroll
+                for (int s = 0; s < H; ++s) {
+                    float v = xraw[0][s];
+#pragma unroll
+                    for (int q = 1; q < NB; ++q)
+                        if (pb == q) v = xraw[q][s];
+                    xs[s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src & 31));
+                    xs[H + s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), (src & 31) + 32));
+                }
+                const int arg = exact_argmin_wave<DP>(xs, crun, CS, c.k0 + srl);
                 if (lane == src) {
-                    pend3 &= pend3 - 1u;
+                    pend &= pend - 1u;
 #pragma unroll
                     for (int i = 0; i < NBST; ++i)
                         if (i == idx) m1[i / ST][i % ST] = arg;
                 }
-                todo = __ballot(pend3 != 0u);
+                todo = __ballot(pend != 0u);
             }
         }
 
