@@ -23,13 +23,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix
+MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix (for scale: the fp32 contraction runs as fp16 pieces)
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix: the pipeline the distance tiles run on
 
 # HBM bytes of one lloyd_step_kernel launch from rocprofv3 counters (profiles/lloyd_step_whole_layer_hbm_counters.md):
 # FETCH_SIZE / WRITE_SIZE in KiB per dispatch and the factors a plain 1 GiB copy gives for each counter.  Valid
 # only for the library version the counters were taken with; any other version reports traffic = null.
 HBM_COUNTERS = {
-    "whole_layer": {"version": 102, "fetch_kib": 330433.3, "write_kib": 55462.7, "fetch_scale": 2.0, "write_scale": 1.0},
+    "whole_layer": {"version": 104, "fetch_kib": 170110.8, "write_kib": 58550.6, "fetch_scale": 2.0, "write_scale": 1.0},
 }
 
 
@@ -176,13 +177,18 @@ def main() -> int:
     alg_flops = 2.0 * w.d * sum_k * w.N * B               # 2*d*k flops per point and (k, round)
     gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
     tflops = alg_flops / (kernel_ms * 1e-3) / 1e12
-    hbm_time, mfma_time = alg_bytes / (HBM_PEAK_GBS * 1e9), alg_flops / (MFMA_F32_PEAK_TFLOPS * 1e12)
+    # The contraction is carried out on the fp16 matrix pipeline: per distance three products of fp16 pieces over the
+    # padded features plus one bias step of 16.  Which roofline is the higher floor for the algorithmic work?
+    d_pad = 8 if w.d <= 8 else (16 if w.d <= 16 else 32)
+    mfma_flops = 2.0 * (3.0 * max(d_pad, 16) + 16.0) * sum_k * w.N * B
+    mfma_tflops = mfma_flops / (kernel_ms * 1e-3) / 1e12
+    hbm_time, mfma_time = alg_bytes / (HBM_PEAK_GBS * 1e9), mfma_flops / (MFMA_F16_PEAK_TFLOPS * 1e12)
     if hbm_time >= mfma_time:
         roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                     "traffic": None}
     else:
-        roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+        roofline = {"bound": "mfma", "achieved": mfma_tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": mfma_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None}
     hc = HBM_COUNTERS.get(w.name)
     if hc is not None and hc["version"] == rls.version() and want_labels:
         hbm_bytes = (hc["fetch_kib"] * hc["fetch_scale"] + hc["write_kib"] * hc["write_scale"]) * 1024.0
@@ -192,7 +198,8 @@ def main() -> int:
     roofline["algorithmic_bytes_per_launch"] = alg_bytes
     roofline.update({"kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_ms,
                      "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
-                     "algorithmic_TFLOPs": tflops, "mfma_f32_frac": tflops / MFMA_F32_PEAK_TFLOPS})
+                     "algorithmic_TFLOPs": tflops, "fp32_mfma_equivalent_frac": tflops / MFMA_F32_PEAK_TFLOPS,
+                     "mfma_f16_TFLOPs": mfma_tflops, "mfma_f16_frac": mfma_tflops / MFMA_F16_PEAK_TFLOPS})
 
     out = {
         "metric": "config_iter_per_s", "value": value, "unit": "config*iter/s", "n_gpus": 1,

@@ -5,14 +5,14 @@
 // stages its group's operand rows, a copy of its centroids and integer accumulators in LDS once; then each of
 // its eight waves works through its own points without any barrier:
 //   load     each lane loads its half of the features of its points straight into registers, one step ahead
-//   assign   distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means, on the
-//            bf16 matrix pipeline: every fp32 operand is split exactly into three bf16 pieces and the six
-//            leading cross products are accumulated in fp32 (fp32-class accuracy; the bf16 pipeline runs
-//            beside the vector ALU, the fp32 one does not); per point and run the three smallest packed
-//            (value, index) keys are kept.  When the two best are closer than the error bound of these
-//            distances the pair is decided again in fp64 with the direct form sum_l (x_l - c_l)^2 - the
-//            arithmetic that defines the assignment - by the lane itself if the third key is clear of the
-//            bound, else by a scan of the whole run; labels never depend on fp32 or bf16 rounding
+//   assign   distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means and scaled
+//            by one power of two into fp16 range, on the 16-bit matrix pipeline: every fp32 operand is split
+//            into two fp16 pieces (22 significant bits) and the three leading cross products are accumulated
+//            in fp32 (fp32-class accuracy; the 16-bit pipeline runs beside the vector ALU, the fp32 one does
+//            not); per point and run the two smallest packed (value, index) keys are kept.  When they are
+//            closer than the error bound of these distances the pair is decided again in fp64 with the direct
+//            form sum_l (x_l - c_l)^2 - the arithmetic that defines the assignment - by a scan of the whole
+//            run; labels never depend on fp32 or fp16 rounding
 //   update   exact centroid sums, kept as running totals: only points whose label differs from the one
 //            of the previous round move their fixed-point row from the old cluster's int64 accumulators
 //            to the new one's (integer LDS atomics; integer adds commute and cancel exactly, so the totals
@@ -27,6 +27,7 @@ namespace rls {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -36,15 +37,20 @@ constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding r
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
 constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by the main accumulator
 constexpr int kLowBits = 36;                  // further bits kept by the low accumulator (wide columns)
+// The centred data is scaled by a power of two so that |x'| <= 2^14 and |2 c'| <= 2^15 fit fp16; an fp16 piece
+// below 2^-14 (subnormal) may be lost, which costs a distance at most 0.078 d + S 2^-24 in scaled units (see eps_a)
+constexpr int kScaledMsb = 14;
+constexpr float kTolFloor = 8.0f;             // twice that loss at d = 32, in scaled squared units
+constexpr int kColScaleOff = 400;             // byte offset of the scale factor in the column info block
 
 __host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 256 : 512; }
 // 32-point blocks a wave takes per slab: two, except at d_pad = 32 with many runs side by side, where the best keys
 // of 4 runs x 2 blocks would not fit the registers next to the operands
 __host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp == 32 && s < 4 ? 1 : 2; }
-// MFMA operands: a lane holds 8 bf16 values of its half of the features per K-step (v_mfma_f32_32x32x16_bf16);
-// a 32-row tile stores, per K-step, the three pieces (high, middle, low) of -2c', and then one bias slot.
+// MFMA operands: a lane holds 8 fp16 values of its half of the features per K-step (v_mfma_f32_32x32x16_f16);
+// a 32-row tile stores, per K-step, the two pieces (high, low) of -2c', and then one bias slot (bf16).
 __host__ __device__ constexpr int ksteps_of(int dp) { return dp == 32 ? 2 : 1; }
-__host__ __device__ constexpr int tile_slots_of(int dp) { return 3 * ksteps_of(dp) + 1; }          // 16-byte slots per lane
+__host__ __device__ constexpr int tile_slots_of(int dp) { return 2 * ksteps_of(dp) + 1; }          // 16-byte slots per lane
 __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(dp) * 64 * 16; }    // per 32-row tile
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
@@ -222,27 +228,27 @@ __device__ inline void split3(float v, unsigned &h, unsigned &m, unsigned &l)
     l = __float_as_uint(r2) >> 16;
 }
 
-// The same exact split for two values at once, with the packed conversion (round to nearest even): each result
-// holds a's piece in its low half and b's in its high half, as two neighbouring operand elements.  With nearest
-// rounding the remainders are even smaller than with truncation (a - h needs 16 bits, a - h - m needs 8), so
-// h + m + l is still exactly the value.
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ inline unsigned cvt_pk_bf16(float a, float b)
-{
-    const f32x2 v = {a, b};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
-}
-__device__ inline void split3_pair(float a, float b, unsigned &h, unsigned &m, unsigned &l)
-{
-    h = cvt_pk_bf16(a, b);
-    const float ra = a - __uint_as_float(h << 16), rb = b - __uint_as_float(h & 0xffff0000u);
-    m = cvt_pk_bf16(ra, rb);
-    const float sa = ra - __uint_as_float(m << 16), sb = rb - __uint_as_float(m & 0xffff0000u);
-    l = cvt_pk_bf16(sa, sb);
-}
-
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+
+// Two fp16 pieces of a value, rounded toward zero: v = h + l + r with |r| < 2^-20 |v| while the pieces are normal
+// fp16 numbers (11 significant bits each; v - h is exact in fp32).  The pair form packs a's pieces into the low
+// halves and b's into the high halves, as two neighbouring operand elements.
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+__device__ inline void split2_pair(float a, float b, unsigned &h, unsigned &l)
+{
+    const fp16x2 hh = __builtin_amdgcn_cvt_pkrtz(a, b);
+    h = __builtin_bit_cast(unsigned, hh);
+    const float ra = a - (float)hh[0], rb = b - (float)hh[1];
+    l = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(ra, rb));
+}
+__device__ inline void split2(float v, unsigned short &h, unsigned short &l)
+{
+    unsigned ph, pl;
+    split2_pair(v, 0.0f, ph, pl);
+    h = (unsigned short)(ph & 0xffffu);
+    l = (unsigned short)(pl & 0xffffu);
+}
 
 // The index that phase A packs into the low 7 bits of a key is the centroid index within the run:
 // centroid j lives in tile (j/4)/S, slot (j/4)%S of its run, row j%4 (see GroupDesc).
@@ -298,7 +304,8 @@ struct WaveCtx {
     const float *cs;              // LDS: the group's centroids as given, rows of DP + 4 floats, zero past feature d
     unsigned long long *sums;     // LDS: fixed-point sum deltas [row][DP + 1]
     int *cnts;                    // LDS: member count deltas [row]
-    const float *mu_s;            // LDS: column means [32]
+    const float *mu_s;            // LDS: -(column mean * scale) [32]
+    float scale;                  // power of two that brings the centred data into fp16 range
     const int *shift_s;           // LDS: fixed-point shifts [32]
     const int *wide_s;            // LDS: wide-column flags [32], any at [32]
     const float *cnmax_s;         // LDS: per-run maximum squared norm of the centred centroids [8]
@@ -329,7 +336,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     constexpr int HP = 8 * NK;                      // feature slots per half-wave (H padded to whole K-steps)
     constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);   // runs owned by a lane
     constexpr int SLAB_ = 32 * NB;                  // points a wave takes at a time
-    constexpr int NM = 6 * NK + 1;                  // MFMAs per tile block
+    constexpr int NM = 3 * NK + 1;                  // MFMAs per tile block
     constexpr int VPER = (48 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
     constexpr bool LOSS = FINAL || TRACE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -411,7 +418,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     // part of the error bound that belongs to a run (the centroids' largest squared norm), per run this lane owns
     float tol_run[ST];
 #pragma unroll
-    for (int st = 0; st < ST; ++st) tol_run[st] = c.eps_a * c.cnmax_s[S == 8 ? 0 : hl * ST + st] + 1.0e-30f;
+    for (int st = 0; st < ST; ++st) tol_run[st] = c.eps_a * c.cnmax_s[S == 8 ? 0 : hl * ST + st] + kTolFloor;
     double jown[ST];                                 // loss sums of the runs this lane owns
 #pragma unroll
     for (int st = 0; st < ST; ++st) jown[st] = 0.0;
@@ -440,9 +447,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         }
         const int nxt2 = grab();
 
-        // ---- B operands of this lane's points: three bf16 pieces of x' per K-step, and the bias slot
-        // (|x'|^2 in pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
-        bf16x8 bx[NB][3][NK], bb[NB];
+        // ---- B operands of this lane's points: two fp16 pieces of the centred, scaled x' per K-step, and the bias
+        // slot in bf16 (|x'|^2 in three pieces on the upper half-wave, ones on the lower: it meets (1,1,1 | pieces of |c'|^2))
+        f16x8 bx[NB][2][NK];
+        bf16x8 bb[NB];
         float xn[NB];
         int m1[NB][ST], m2[NB][ST];
         int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
@@ -452,18 +460,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             float part = 0.0f;
 #pragma unroll
             for (int s = 0; s < HP; ++s) {
-                xc[s] = s < H ? xraw[pb][s] - c.mu_s[f0 + s] : 0.0f;
+                xc[s] = s < H ? fmaf(xraw[pb][s], c.scale, c.mu_s[f0 + s]) : 0.0f;   // (x - mean) * scale, one rounding
                 part = fmaf(xc[s], xc[s], part);
             }
             xn[pb] = part + xchg32(part);
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
-                unsigned ph[4], pm[4], pl[4];
+                unsigned ph[4], pl[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) split3_pair(xc[8 * ks + 2 * i], xc[8 * ks + 2 * i + 1], ph[i], pm[i], pl[i]);
-                bx[pb][0][ks] = as_bf16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
-                bx[pb][1][ks] = as_bf16x8(make_uint4(pm[0], pm[1], pm[2], pm[3]));
-                bx[pb][2][ks] = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+                for (int i = 0; i < 4; ++i) split2_pair(xc[8 * ks + 2 * i], xc[8 * ks + 2 * i + 1], ph[i], pl[i]);
+                bx[pb][0][ks] = as_f16x8(make_uint4(ph[0], ph[1], ph[2], ph[3]));
+                bx[pb][1][ks] = as_f16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
             }
             unsigned nh, nm, nl;
             split3(xn[pb], nh, nm, nl);
@@ -483,16 +490,16 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         // ---- distances tile by tile; the results of one block are folded while the matrix pipeline runs the next
         // (the tile loop is written out twice so that the operand buffers and accumulators alternate by name
         // instead of being copied)
-        bf16x8 a_even[NS], a_odd[NS];
-        auto load_a = [&](bf16x8 (&dst)[NS], int t) {
+        uint4 a_even[NS], a_odd[NS];
+        auto load_a = [&](uint4 (&dst)[NS], int t) {
 #pragma unroll
-            for (int sl = 0; sl < NS; ++sl) dst[sl] = as_bf16x8(opA_s[(t * NS + sl) * 64 + lane]);
+            for (int sl = 0; sl < NS; ++sl) dst[sl] = opA_s[(t * NS + sl) * 64 + lane];
         };
         load_a(a_even, 0);
         floatx16 acc_prev;                 // results of the block before the current one, folded one block late
         int kidx_old[16];
         // `first`: the very first block of the slab has no block before it to fold
-        auto tile_step = [&](const bf16x8 (&a_cur)[NS], bf16x8 (&a_nxt)[NS], int t, auto first) {
+        auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto first) {
             load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
             // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
             int kidx[16];
@@ -506,18 +513,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
                 floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // m.m
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // l.h
 #pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[2 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // l.h
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][1][ks], acc, 0, 0, 0);   // h.l
 #pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][2][ks], acc, 0, 0, 0);   // h.l
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[1 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // m.h
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][1][ks], acc, 0, 0, 0);   // h.m
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[0 * NK + ks], bx[pb][0][ks], acc, 0, 0, 0);   // h.h
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur[3 * NK], bb[pb], acc, 0, 0, 0);                                              // norms
+                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // h.h
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2 * NK]), bb[pb], acc, 0, 0, 0);                                         // norms
                 if (pb == 0) {
                     if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
                 } else {
@@ -816,7 +817,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         const float *colmean = reinterpret_cast<const float *>(wsb + a.off_colinfo);
         const int *colshift = reinterpret_cast<const int *>(wsb + a.off_colinfo + 128);
         const int *colwide = reinterpret_cast<const int *>(wsb + a.off_colinfo + 256);
-        if (tid < 32) { mu_s[tid] = tid < DP ? colmean[tid] : 0.0f; shift_s[tid] = colshift[tid]; }
+        if (tid < 32) { mu_s[tid] = tid < DP ? colmean[tid] : 0.0f; shift_s[tid] = colshift[tid]; }   // colmean: already negated and scaled
         if (tid < 33) wide_s[tid] = colwide[tid];
         const uint4 *src = reinterpret_cast<const uint4 *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
         for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
@@ -841,6 +842,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
     c.next_slab = next_slab;
     c.sums = sums; c.cnts = cnts; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
+    c.scale = *reinterpret_cast<const float *>(wsb + a.off_colinfo + kColScaleOff);
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
     c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
     c.labels_out = (FINAL && a.labels) ? a.labels + (int64_t)b * a.lab_bs + (int64_t)g.run0 * a.N : nullptr;
@@ -850,10 +852,14 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     // 16-byte loads need whole quads of features and aligned rows
     c.first_round = a.first_round != 0;
     c.vec_x = (d % 4 == 0) && (a.ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
-    // Bound on the summed error of two matrix-pipeline distances, relative to S = |x'|^2 + max |c'|^2.  Per
-    // distance: dropped piece products 2^-23 S; 7 or 13 chained MFMAs, each charged five fp32 roundings of a
-    // partial sum of at most 2 S (35 or 65 times 2^-23 S); fp32 norms d_pad 2^-24 S each; centring 2 2^-23 S:
-    // 46 2^-23 S at d_pad <= 16 and 84 2^-23 S at 32.  Twice that is 92 and 168; the bound used is 120 and 200.
+    // Bound on the summed error of two matrix-pipeline distances, relative to S = |x'|^2 + max |c'|^2 (centred and
+    // scaled).  Per distance: what the two fp16 pieces per operand leave out - the product of the two low pieces and
+    // the two remainders, each below 2^-20 of its element product - is at most 3 2^-20 |x'| |2c'| <= 24 2^-23 S; 4 or 7
+    // chained MFMAs, each charged five fp32 roundings of a partial sum of at most 2 S (20 or 35 times 2^-23 S); fp32
+    // norms d_pad 2^-24 S each; centring 2 2^-23 S: 54.5 2^-23 S at d_pad <= 16 and 77.5 2^-23 S at 32.  Twice that
+    // is 109 and 155; the bound used is 120 and 200.  A piece below 2^-14 (an fp16 subnormal) is counted as lost
+    // altogether: per distance at most 2^-14 sqrt(d) (|x'| + |2c'|) <= 2^-24 S + 0.078 d, hence the absolute term
+    // kTolFloor next to the relative one (the 2^-24 S makes the 24 above 24.5).
     c.eps_a = (float)(5 * ((DP < 16 ? 16 : DP) + 8)) * 1.1920928955078125e-07f;   // 5 (max(DP, 16) + 8) 2^-23
 
     double jloc[8];
@@ -951,7 +957,7 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     __syncthreads();
     const ColPart *part = reinterpret_cast<const ColPart *>(ws + (int64_t)b * ws_bs + off_part);
     float mean = 0.0f;
-    int shift = 0, wide = 0;
+    int shift = 0, wide = 0, msb = -(1 << 20);
     if (l < d) {
         ColPart t = part[l];
         for (int g = 1; g < n_blocks; ++g) {
@@ -964,6 +970,7 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
         if (t.bad) atomicOr(&flags, RLS_STATUS_NONFINITE);
         else {
             mean = (float)(t.sum / (double)N);
+            msb = t.max_msb;
             if (t.max_msb >= t.min_lsb) {
                 // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk moves
                 // at most 2^17 rows in and out of a cluster within 63 bits. Bits below the grid (wide columns) go to
@@ -979,9 +986,17 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     float *colmean = reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo);
     int *colshift = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 128);
     int *colwide = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 256);
-    colmean[l] = mean;
+    // One power of two for all columns (distances keep their order): with |x| < 2^(M+1) in every column, and so
+    // |mean| <= 2^(M+1), the centred values obey |x - mean| * 2^(kScaledMsb - M - 2) <= 2^kScaledMsb.  The exponent
+    // is kept inside the fp32 range; data that small only makes every comparison a close call.
+    for (int off = 16; off >= 1; off >>= 1) msb = max(msb, __shfl_xor(msb, off, 64));
+    int e = kScaledMsb - 2 - (msb > -(1 << 20) ? msb : 0);
+    e = min(max(e, -100), 100);
+    const float scale = ldexpf(1.0f, e);
+    colmean[l] = -(mean * scale);      // what the kernels add after multiplying by the scale
     colshift[l] = shift;
     colwide[l] = wide;
+    if (l == 0) *reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo + kColScaleOff) = scale;
     if (wide) atomicOr(&flags, 1 << 16);
     __syncthreads();
     if (l == 0) { colwide[32] = (flags >> 16) & 1; status[b] = flags & 0xffff; }
@@ -1103,11 +1118,12 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
     const GroupDesc g = plan.g[gi];
     const int rl = run - g.run0;
     char *wsb = a.ws + (int64_t)b * a.ws_bs;
-    const float *colmean = reinterpret_cast<const float *>(wsb + a.off_colinfo);
+    const float *colmean = reinterpret_cast<const float *>(wsb + a.off_colinfo);   // -(mean * scale)
     const int *colshift = reinterpret_cast<const int *>(wsb + a.off_colinfo + 128);
     const int *colwide = reinterpret_cast<const int *>(wsb + a.off_colinfo + 256);
+    const float scale = *reinterpret_cast<const float *>(wsb + a.off_colinfo + kColScaleOff);
     float *Cb = a.C + (int64_t)b * a.c_bs;
-    // operand block of the group: per tile, tile_slots_of(DP) slots of 64 lanes x 8 bf16
+    // operand block of the group: per tile, tile_slots_of(DP) slots of 64 lanes x 8 halves (fp16 pieces, bf16 bias)
     unsigned short *opA = reinterpret_cast<unsigned short *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
     constexpr int NK = ksteps_of(DP), NS = tile_slots_of(DP);
 
@@ -1207,7 +1223,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
                     c = Cb[(int64_t)(row0 + j) * d + l];     // a cluster without members keeps its centroid
                 }
             }
-            cp = c - colmean[l];
+            cp = fmaf(c, scale, colmean[l]);     // (c - mean) * scale, one rounding, as for the points
         }
         cs[j * DP + l] = cp;
         // operand position of (centroid j, feature l)
@@ -1215,12 +1231,11 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         const int t = qd / g.S, slot = rl * g.S + qd % g.S;
         const int m = 8 * (slot & 3) + 4 * (slot >> 2) + i;
         const int h = l / (DP / 2), sf = l % (DP / 2);
-        unsigned ph, pm, pl;
-        split3(-2.0f * cp, ph, pm, pl);
+        unsigned short ph, pl;
+        split2(-2.0f * cp, ph, pl);
         const int ks = sf >> 3, el = sf & 7, ln = h * 32 + m;
-        opA[((int64_t)(t * NS + 0 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)ph;
-        opA[((int64_t)(t * NS + 1 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)pm;
-        opA[((int64_t)(t * NS + 2 * NK + ks) * 64 + ln) * 8 + el] = (unsigned short)pl;
+        opA[((int64_t)(t * NS + 0 * NK + ks) * 64 + ln) * 8 + el] = ph;
+        opA[((int64_t)(t * NS + 1 * NK + ks) * 64 + ln) * 8 + el] = pl;
     }
     __syncthreads();
     float mx = 0.0f;
@@ -1233,7 +1248,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         unsigned ph, pm, pl;
         split3(nrm, ph, pm, pl);
         const int m = 8 * (slot & 3) + 4 * (slot >> 2) + i;
-        unsigned short *bias = opA + ((int64_t)(t * NS + 3 * NK) * 64 + m) * 8;
+        unsigned short *bias = opA + ((int64_t)(t * NS + 2 * NK) * 64 + m) * 8;
         bias[0] = (unsigned short)ph; bias[1] = (unsigned short)pm; bias[2] = (unsigned short)pl;
         mx = fmaxf(mx, nrm);
     }
