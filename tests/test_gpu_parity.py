@@ -377,6 +377,37 @@ def test_sweep_wide_columns(rls, orc):
     assert compare_sweep(orc, X, res, ref, 1, 9) == 0
 
 
+@pytest.mark.parametrize("case", ["scale_up", "scale_down", "offset", "mixed_columns", "small_next_to_big", "d32_offset"])
+def test_sweep_value_ranges(rls, orc, case):
+    """The matrix path works on centred data scaled by a power of two into 16-bit range: magnitudes far from 1, means
+    far from the spread, and columns that all but vanish next to the largest one must give the oracle's results
+    (within what the oracle's exact sums hold: |x| < 2^40, multiples of 2^-60)."""
+    rng = np.random.default_rng(700 + len(case) * 13 + ord(case[0]))
+    N, d = 4000, 16
+    centres = rng.standard_normal((12, d)) * 3.0
+    X = centres[rng.integers(0, 12, size=N)] + rng.standard_normal((N, d)) * 0.4
+    if case == "scale_up":
+        X = X * 2.0 ** 33 * 1.37
+    elif case == "scale_down":
+        X = X * 2.0 ** -14 * 0.81
+    elif case == "offset":
+        X = X * 1.0e-3 + 4096.5              # mean 4e6 times the spread: fp32 keeps about 12 bits of the spread
+    elif case == "mixed_columns":
+        X = X * (10.0 ** rng.integers(-5, 7, size=d))[None, :]
+    elif case == "small_next_to_big":
+        X[:, 0] *= 1.0e4                     # the other columns fall below the fp16 range after scaling
+        X[:, 1:] *= 1.0e-4
+        X[:, 0] = np.round(X[:, 0] / 2.0e4) * 2.0e4      # and decide between points that tie in the big column
+    elif case == "d32_offset":
+        d = 32
+        centres = rng.standard_normal((12, d)) * 3.0
+        X = centres[rng.integers(0, 12, size=N)] + rng.standard_normal((N, d)) * 0.4 + 1000.0
+    X = X.astype(np.float32)
+    res, ref = run_both(rls, orc, X, 1, 20, 6, seed=3)
+    assert int(res.status.item()) == 0
+    assert compare_sweep(orc, X, res, ref, 1, 20) == 0
+
+
 @pytest.mark.parametrize("name,N,k_min,k_max,k_wave,const", [
     ("tiny", None, 1, 16, 8, 1.05), ("tiny", None, 1, 16, 3, 1.5), ("tiny", None, 2, 16, 5, 1.0001),
     ("mid", 20000, 1, 40, 8, 1.05), ("mid", 20000, 8, 63, 16, 1.02), ("mid", 20000, 1, 24, 8, 1e9)])
