@@ -1040,6 +1040,36 @@ __global__ void sweep_init_kernel(InitArgs a)
     for (int64_t e = t0; e < a.n_prev16; e += step) prev[e] = none;
 }
 
+// Adds the per-chunk deltas of one (centroid, feature) element for chunks [c_begin, c_end) to a 128-bit sum and the
+// member count deltas to cnt.  The values sit a whole chunk block apart in memory: eight loads are kept in flight,
+// the walk is bound by their latency (integer sums: any order gives the same result).
+__device__ inline void sum_chunks(const long long *pe, const int *pc, int64_t estride, int64_t cstride, int c_begin, int c_end,
+                                  long long &hi, unsigned long long &lo, long long &cnt)
+{
+    constexpr int U = 8;
+    int c0 = c_begin;
+    for (; c0 + U <= c_end; c0 += U) {
+        long long v[U];
+        int m[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { v[u] = pe[(c0 + u) * estride]; m[u] = pc[(c0 + u) * cstride]; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long nlo = lo + (unsigned long long)v[u];
+            hi += (v[u] >> 63) + (nlo < lo ? 1 : 0);
+            lo = nlo;
+            cnt += m[u];
+        }
+    }
+    for (; c0 < c_end; ++c0) {
+        const long long v = pe[c0 * estride];
+        const unsigned long long nlo = lo + (unsigned long long)v;
+        hi += (v >> 63) + (nlo < lo ? 1 : 0);
+        lo = nlo;
+        cnt += pc[c0 * cstride];
+    }
+}
+
 // 128-bit two's complement sum (hi, lo) -> fp64 with one round-to-nearest-even, scaled by 2^-shift
 __device__ inline double fixed128_to_double(long long hi, unsigned long long lo, int shift)
 {
@@ -1140,13 +1170,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
             const long long *psum = reinterpret_cast<const long long *>(wsb + a.off_psum) + (int64_t)(row0 + j) * d + l;
             const int *pcnt = reinterpret_cast<const int *>(wsb + a.off_pcnt) + row0 + j;
             const int c_begin = (int)((int64_t)plan.n_chunks * sl / nsl), c_end = (int)((int64_t)plan.n_chunks * (sl + 1) / nsl);
-            for (int c0 = c_begin; c0 < c_end; ++c0) {
-                const long long v = psum[(int64_t)c0 * plan.total_rows * d];
-                const unsigned long long nlo = lo + (unsigned long long)v;
-                hi += (v >> 63) + (nlo < lo ? 1 : 0);
-                lo = nlo;
-                cnt += pcnt[(int64_t)c0 * plan.total_rows];
-            }
+            sum_chunks(psum, pcnt, (int64_t)plan.total_rows * d, plan.total_rows, c_begin, c_end, hi, lo, cnt);
         }
         part_hi[tid] = hi; part_lo[tid] = lo; part_cnt[tid] = cnt;
         __syncthreads();
@@ -1177,30 +1201,8 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
                         cnt += part_cnt[sl * E + e];
                     }
                 } else {
-                    const long long *pe = psum + (int64_t)(row0 + j) * d + l;
-                    const int *pc = pcnt + row0 + j;
-                    const int64_t cstride = (int64_t)plan.total_rows * d;
-                    int c0 = 0;
-                    for (; c0 + 4 <= plan.n_chunks; c0 += 4) {   // four loads in flight
-                        long long v[4];
-                        int m[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) { v[u] = pe[(c0 + u) * cstride]; m[u] = pc[(int64_t)(c0 + u) * plan.total_rows]; }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const unsigned long long nlo = lo + (unsigned long long)v[u];
-                            hi += (v[u] >> 63) + (nlo < lo ? 1 : 0);
-                            lo = nlo;
-                            cnt += m[u];
-                        }
-                    }
-                    for (; c0 < plan.n_chunks; ++c0) {
-                        const long long v = pe[c0 * cstride];
-                        const unsigned long long nlo = lo + (unsigned long long)v;
-                        hi += (v >> 63) + (nlo < lo ? 1 : 0);
-                        lo = nlo;
-                        cnt += pc[(int64_t)c0 * plan.total_rows];
-                    }
+                    sum_chunks(psum + (int64_t)(row0 + j) * d + l, pcnt + row0 + j, (int64_t)plan.total_rows * d,
+                               plan.total_rows, 0, plan.n_chunks, hi, lo, cnt);
                 }
                 tot[0] = hi;
                 tot[1] = (long long)lo;
