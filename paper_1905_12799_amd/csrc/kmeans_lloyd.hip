@@ -61,7 +61,7 @@ __host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_
 {
     Carve c;
     int off = 0;
-    c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (bf16 pieces + bias)
+    c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (fp16 pieces + bias slot)
     c.cs = off;      off += real_rows * (dp + 4) * 4;                   // centroids as given, rows of dp + 4 floats, zero-padded
     c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point sum deltas
     c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas

@@ -408,6 +408,53 @@ def test_sweep_value_ranges(rls, orc, case):
     assert compare_sweep(orc, X, res, ref, 1, 20) == 0
 
 
+def random_sweep_case(rng):
+    """One random shape and data kind: clustered, small integers, duplicates, knob-like lattices, scaled, shifted."""
+    d = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 12, 16, 17, 24, 32]))
+    N = int(rng.choice([65, 200, 513, 1000, 2049, 5000]))
+    k_max = int(min(N, rng.choice([1, 3, 8, 9, 17, 33, 64, 65, 100, 128])))
+    k_min = int(rng.integers(1, k_max + 1)) if rng.random() < 0.5 else 1
+    iters = int(rng.integers(0, 6))
+    kind = str(rng.choice(["gauss", "int", "dup", "mixed", "const_col", "scaled", "offset", "colmix", "knob"]))
+    blobs = rng.uniform(-30, 30, size=(9, d))[rng.integers(0, 9, N)] + rng.standard_normal((N, d))
+    if kind == "gauss":
+        X = blobs
+    elif kind == "int":
+        X = rng.integers(0, 4, size=(N, d)).astype(np.float64)
+    elif kind == "dup":
+        base = rng.standard_normal((max(2, N // 50), d)) * 5
+        X = base[rng.integers(0, len(base), N)]
+    elif kind == "mixed":
+        X = rng.standard_normal((N, d))
+        X[:, 0] = rng.integers(0, 3, N)
+        X *= rng.choice([1e-3, 1.0, 1e3])
+    elif kind == "scaled":
+        X = blobs * 2.0 ** int(rng.integers(-12, 30))
+    elif kind == "offset":
+        X = blobs * 0.1 * 2.0 ** int(rng.integers(-8, 4)) + float(rng.choice([100.0, 4096.5, -70000.25]))
+    elif kind == "colmix":
+        X = blobs * (2.0 ** rng.integers(-10, 20, size=d))[None, :]
+    elif kind == "knob":
+        sizes = rng.integers(2, 200, size=d)
+        c = rng.uniform(0, 1, size=(12, d)) * sizes
+        X = np.clip(np.round(c[rng.integers(0, 12, N)] + rng.standard_normal((N, d)) * np.maximum(0.5, 0.08 * sizes)), 0, sizes - 1)
+    else:
+        X = rng.standard_normal((N, d))
+        X[:, -1] = 7.25
+    return X.astype(np.float32), k_min, k_max, iters, kind, int(rng.integers(0, 1 << 30))
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_sweep_randomized(rls, orc, seed):
+    rng = np.random.default_rng(seed)
+    for case in range(30):
+        X, k_min, k_max, iters, kind, s = random_sweep_case(rng)
+        print(f"case {case}: N={X.shape[0]} d={X.shape[1]} k={k_min}..{k_max} iters={iters} kind={kind} seed={s}", flush=True)
+        res, ref = run_both(rls, orc, X, k_min, k_max, iters, seed=s)
+        assert int(res.status.item()) == 0
+        compare_sweep(orc, X, res, ref, k_min, k_max)
+
+
 @pytest.mark.parametrize("name,N,k_min,k_max,k_wave,const", [
     ("tiny", None, 1, 16, 8, 1.05), ("tiny", None, 1, 16, 3, 1.5), ("tiny", None, 2, 16, 5, 1.0001),
     ("mid", 20000, 1, 40, 8, 1.05), ("mid", 20000, 8, 63, 16, 1.02), ("mid", 20000, 1, 24, 8, 1e9)])
