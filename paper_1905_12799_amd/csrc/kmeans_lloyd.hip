@@ -37,8 +37,8 @@ constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding r
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
 constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by the main accumulator
 constexpr int kLowBits = 36;                  // further bits kept by the low accumulator (wide columns)
-// The centred data is scaled by a power of two so that |x'| <= 2^14 and |2 c'| <= 2^15 fit fp16; an fp16 piece
-// below 2^-14 (subnormal) may be lost, which costs a distance at most 0.078 d + S 2^-24 in scaled units (see eps_a)
+// The centred data is scaled by a power of two so that |x'| < 2^13 and |2 c'| < 2^14 sit well inside fp16; an fp16
+// piece below 2^-14 (subnormal) may be lost, which costs a distance at most 0.078 d + S 2^-24 in scaled units (see eps_a)
 constexpr int kScaledMsb = 14;
 constexpr float kTolFloor = 8.0f;             // twice that loss at d = 32, in scaled squared units
 constexpr int kColScaleOff = 400;             // byte offset of the scale factor in the column info block
@@ -905,6 +905,8 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
 struct ColPart {
     double sum;
     int min_lsb, max_msb, bad, pad;
+    float vmin, vmax;     // smallest and largest finite value
+    int pad2[2];
 };
 
 __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restrict__ X, int64_t N, int d, int dp, int64_t ldx,
@@ -917,7 +919,7 @@ __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restr
     const int l = tid % dp, pg = tid / dp, ppp = kThreads / dp;
     const int64_t per = (N + gridDim.x - 1) / gridDim.x;
     const int64_t r0 = (int64_t)blockIdx.x * per, r1 = min(N, r0 + per);
-    ColPart c = {0.0, 1 << 20, -(1 << 20), 0, 0};
+    ColPart c = {0.0, 1 << 20, -(1 << 20), 0, 0, INFINITY, -INFINITY, {0, 0}};
     if (l < d) {
         for (int64_t r = r0 + pg; r < r1; r += ppp) {
             const float x = Xb[r * ldx + l];
@@ -926,6 +928,8 @@ __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restr
             unsigned m = u & 0x7fffffu;
             if (e == 255) { c.bad = 1; continue; }
             c.sum = __dadd_rn(c.sum, (double)x);
+            c.vmin = fminf(c.vmin, x);
+            c.vmax = fmaxf(c.vmax, x);
             if (e == 0) { if (m == 0) continue; e = 1; } else m |= 0x800000u;
             const int lsb = e - 150 + (__ffs((int)m) - 1);
             const int msb = e - 150 + (31 - __clz((int)m));
@@ -943,6 +947,8 @@ __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restr
             t.min_lsb = min(t.min_lsb, o.min_lsb);
             t.max_msb = max(t.max_msb, o.max_msb);
             t.bad |= o.bad;
+            t.vmin = fminf(t.vmin, o.vmin);
+            t.vmax = fmaxf(t.vmax, o.vmax);
         }
         reinterpret_cast<ColPart *>(ws + (int64_t)b * ws_bs + off_part)[blockIdx.x * 32 + tid] = t;
     }
@@ -966,11 +972,16 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
             t.min_lsb = min(t.min_lsb, o.min_lsb);
             t.max_msb = max(t.max_msb, o.max_msb);
             t.bad |= o.bad;
+            t.vmin = fminf(t.vmin, o.vmin);
+            t.vmax = fmaxf(t.vmax, o.vmax);
         }
         if (t.bad) atomicOr(&flags, RLS_STATUS_NONFINITE);
         else {
             mean = (float)(t.sum / (double)N);
-            msb = t.max_msb;
+            // largest distance of a value (or of a centroid, which lies between the extremes) from the mean; the
+            // exponent of the next power of two above it, with the rounding of the two differences allowed for
+            const float reach = fmaxf(t.vmax - mean, mean - t.vmin) * 1.000001f;
+            if (reach > 0.0f) msb = ilogbf(reach);
             if (t.max_msb >= t.min_lsb) {
                 // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk moves
                 // at most 2^17 rows in and out of a cluster within 63 bits. Bits below the grid (wide columns) go to
@@ -986,9 +997,9 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     float *colmean = reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo);
     int *colshift = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 128);
     int *colwide = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 256);
-    // One power of two for all columns (distances keep their order): with |x| < 2^(M+1) in every column, and so
-    // |mean| <= 2^(M+1), the centred values obey |x - mean| * 2^(kScaledMsb - M - 2) <= 2^kScaledMsb.  The exponent
-    // is kept inside the fp32 range; data that small only makes every comparison a close call.
+    // One power of two for all columns (distances keep their order): with |x - mean| < 2^(M+1) in every column the
+    // centred values obey |x - mean| * 2^(kScaledMsb - M - 2) < 2^(kScaledMsb - 1), one bit inside what fp16 holds for
+    // 2 c'.  The exponent is kept inside the fp32 range; data that small only makes every comparison a close call.
     for (int off = 16; off >= 1; off >>= 1) msb = max(msb, __shfl_xor(msb, off, 64));
     int e = kScaledMsb - 2 - (msb > -(1 << 20) ? msb : 0);
     e = min(max(e, -100), 100);
