@@ -3,7 +3,7 @@
 //
 // Per iteration one launch of lloyd_step_kernel covers every (group of runs, chunk of points).  A workgroup
 // stages its group's operand rows, a copy of its centroids and integer accumulators in LDS once; then each of
-// its eight waves works through its own points without any barrier:
+// its waves (twelve up to d_pad = 16, eight at 32) works through its own points without any barrier:
 //   load     each lane loads its half of the features of its points straight into registers, one step ahead
 //   assign   distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means and scaled
 //            by one power of two into fp16 range, on the 16-bit matrix pipeline: every fp32 operand is split
@@ -31,7 +31,7 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
-constexpr int kThreads = 512;                // one workgroup per CU: 8 waves, 2 per SIMD
+constexpr int kThreads = 512;                // workgroup of the helper kernels (the step kernel: step_threads_of)
 constexpr int kWaves = kThreads / 64;
 constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding rows: never the minimum
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
@@ -44,9 +44,13 @@ constexpr float kTolFloor = 8.0f;             // twice that loss at d = 32, in s
 constexpr int kColScaleOff = 400;             // byte offset of the scale factor in the column info block
 
 __host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 256 : 512; }
-// 32-point blocks a wave takes per slab: two, except at d_pad = 32 with many runs side by side, where the best keys
-// of 4 runs x 2 blocks would not fit the registers next to the operands
-__host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp == 32 && s < 4 ? 1 : 2; }
+// 32-point blocks a wave takes per slab.  Up to d_pad = 16: one, which keeps a wave under 168 registers so that three
+// waves fit a SIMD (measured: 6% shorter launches than two waves with two blocks each).  At d_pad = 32 three waves do
+// not fit; there a wave takes two blocks, except with many runs side by side, where the best keys of 4 runs x 2 blocks
+// would not fit the registers next to the operands.
+__host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp <= 16 ? 1 : (s < 4 ? 1 : 2); }
+// threads of a step workgroup: up to d_pad = 16 one block per slab leaves room for three waves per SIMD
+__host__ __device__ constexpr int step_threads_of(int dp) { return dp <= 16 ? 768 : 512; }
 // MFMA operands: a lane holds 8 fp16 values of its half of the features per K-step (v_mfma_f32_32x32x16_f16);
 // a 32-row tile stores, per K-step, the two pieces (high, low) of -2c', and then one bias slot (bf16).
 __host__ __device__ constexpr int ksteps_of(int dp) { return dp == 32 ? 2 : 1; }
@@ -65,7 +69,7 @@ __host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_
     c.cs = off;      off += real_rows * (dp + 4) * 4;                   // centroids as given, rows of dp + 4 floats, zero-padded
     c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point sum deltas
     c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
-    c.misc = off;    off += 1024;
+    c.misc = off;    off += 2048;
     c.total = off;
     return c;
 }
@@ -295,7 +299,7 @@ __device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int
     }
 }
 
-// Everything a wave needs to run its share of a chunk.  The eight waves of a workgroup share the group's
+// Everything a wave needs to run its share of a chunk.  The waves of a workgroup share the group's
 // operand rows, centroid copy and integer accumulators (LDS), but each wave owns its points from the global
 // load to the accumulator update, so there is no barrier inside the tile loop and waves in different phases
 // (matrix pipeline / vector ALU / LDS atomics) overlap on a SIMD.
@@ -406,7 +410,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 for (int st = 0; st < ST; ++st) asm volatile("" : "+v"(oldn[pb][st]));
         }
     };
-    // The chunk is handed out in slabs of SLAB points: the first eight statically, the rest from a counter in
+    // The chunk is handed out in slabs of SLAB points: one per wave statically, the rest from a counter in
     // LDS, so the waves of the workgroup finish together however their close calls and updates are spread.
     constexpr int SLAB = SLAB_;
     const int n_slabs = (int)((c.chunk_end - c.chunk_begin + SLAB - 1) / SLAB);
@@ -780,9 +784,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 }
 
 template <int DP, bool FINAL, bool TRACE>
-__global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, StepArgs a)
+__global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPlan plan, StepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int TH = step_threads_of(DP), WV = TH / 64;
 
     const int b = blockIdx.y;
     if (a.status[b] != 0) return;
@@ -805,7 +810,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
     float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
     int *next_slab = reinterpret_cast<int *>(smem + cv.misc + 448);
-    double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][kWaves]
+    double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][WV]
 
     const int tid = threadIdx.x;
     char *wsb = a.ws + (int64_t)b * a.ws_bs;
@@ -820,19 +825,19 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
         if (tid < 32) { mu_s[tid] = tid < DP ? colmean[tid] : 0.0f; shift_s[tid] = colshift[tid]; }   // colmean: already negated and scaled
         if (tid < 33) wide_s[tid] = colwide[tid];
         const uint4 *src = reinterpret_cast<const uint4 *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
-        for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += kThreads) opA_s[e] = src[e];
+        for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += TH) opA_s[e] = src[e];
         {
             const float *csrc = Cb + (int64_t)grow0 * d;
-            for (int e = tid; e < real_rows * DP; e += kThreads) {
+            for (int e = tid; e < real_rows * DP; e += TH) {
                 const int j = e / DP, l = e % DP;
                 cs_lds[j * (DP + 4) + l] = l < d ? csrc[j * d + l] : 0.0f;
             }
         }
-        if (tid == 0) *next_slab = kWaves;
+        if (tid == 0) *next_slab = WV;
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
         if (!FINAL) {
-            for (int e = tid; e < real_rows * (DP + 1); e += kThreads) sums[e] = 0ull;
-            for (int e = tid; e < real_rows; e += kThreads) cnts[e] = 0;
+            for (int e = tid; e < real_rows * (DP + 1); e += TH) sums[e] = 0ull;
+            for (int e = tid; e < real_rows; e += TH) cnts[e] = 0;
         }
     }
     __syncthreads();
@@ -880,7 +885,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
             double v = jloc[i];
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v = __dadd_rn(v, __shfl_xor(v, off, 64));
-            if (lane == 0) jpart[i * kWaves + wave] = v;
+            if (lane == 0) jpart[i * WV + wave] = v;
         }
     }
     __syncthreads();   // every wave has finished its points: accumulators and partial losses are complete
@@ -888,14 +893,14 @@ __global__ void __launch_bounds__(kThreads) lloyd_step_kernel(SweepPlan plan, St
     if (!FINAL) {
         unsigned long long *psum = reinterpret_cast<unsigned long long *>(wsb + a.off_psum) +
                                    ((int64_t)chunk * plan.total_rows + grow0) * d;
-        for (int e = tid; e < real_rows * d; e += kThreads) psum[e] = sums[(e / d) * (DP + 1) + e % d];
+        for (int e = tid; e < real_rows * d; e += TH) psum[e] = sums[(e / d) * (DP + 1) + e % d];
         int *pcnt = reinterpret_cast<int *>(wsb + a.off_pcnt) + (int64_t)chunk * plan.total_rows + grow0;
-        for (int e = tid; e < real_rows; e += kThreads) pcnt[e] = cnts[e];
+        for (int e = tid; e < real_rows; e += TH) pcnt[e] = cnts[e];
     }
     if (FINAL || TRACE) {
         if (tid < g.n_runs) {
             double v = 0.0;
-            for (int w = 0; w < kWaves; ++w) v = __dadd_rn(v, jpart[tid * kWaves + w]);
+            for (int w = 0; w < WV; ++w) v = __dadd_rn(v, jpart[tid * WV + w]);
             reinterpret_cast<double *>(wsb + a.off_pj)[(int64_t)chunk * plan.n_runs + g.run0 + tid] = v;
         }
     }
@@ -1348,17 +1353,17 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         sa.first_round = t == 0 ? 1 : 0;
         if (prof) { hipError_t e = profile_mark(s, true); if (e != hipSuccess) return e; }
         if (trace) {
-            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(kThreads), lds, s, plan, sa);
+            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
             hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws,
                                L.per_batch, L.pj, a.trace, (int64_t)plan.n_runs * (a.iters + 1), (int64_t)(a.iters + 1), (int64_t)t);
         } else {
-            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false>), grid, dim3(kThreads), lds, s, plan, sa);
+            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
         }
         hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
     }
-    hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false>), grid, dim3(kThreads), lds, s, plan, sa);
+    hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
     hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws, L.per_batch,
                        L.pj, a.inertia, (int64_t)plan.n_runs, (int64_t)1, (int64_t)0);
     if (trace)
