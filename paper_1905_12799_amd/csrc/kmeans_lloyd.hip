@@ -61,14 +61,16 @@ __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(d
 struct Carve {
     int opA, cs, sums, cnts, misc, total;
 };
-__host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows)
+__host__ __device__ inline Carve carve_lds(int dp, int d, int n_tiles, int real_rows, int copies)
 {
     Carve c;
     int off = 0;
     c.opA = off;     off += n_tiles * tile_bytes_of(dp);       // MFMA operand rows of the group (fp16 pieces + bias slot)
     c.cs = off;      off += real_rows * (dp + 4) * 4;                   // centroids as given, rows of dp + 4 floats, zero-padded
-    c.sums = off;    off += real_rows * (dp + 1) * 8;          // fixed-point sum deltas
-    c.cnts = off;    off += (real_rows * 4 + 15) / 16 * 16;    // member count deltas
+    // accumulators: `copies` of them side by side (a lane adds to copy lane % copies, which spreads the lanes that
+    // hit one cluster of a run with few clusters over several addresses; the copies are summed at the end)
+    c.sums = off;    off += copies * real_rows * (dp + 1) * 8;          // fixed-point sum deltas
+    c.cnts = off;    off += (copies * real_rows * 4 + 15) / 16 * 16;    // member count deltas
     c.misc = off;    off += 2048;
     c.total = off;
     return c;
@@ -306,8 +308,9 @@ __device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int
 struct WaveCtx {
     const uint4 *opA_s;           // LDS: operand slots of the group's tiles
     const float *cs;              // LDS: the group's centroids as given, rows of DP + 4 floats, zero past feature d
-    unsigned long long *sums;     // LDS: fixed-point sum deltas [row][DP + 1]
-    int *cnts;                    // LDS: member count deltas [row]
+    unsigned long long *sums;     // LDS: fixed-point sum deltas [copy][row][DP + 1]
+    int *cnts;                    // LDS: member count deltas [copy][row]
+    int copies, real_rows;        // accumulator copies (a power of two) and rows per copy
     const float *mu_s;            // LDS: -(column mean * scale) [32]
     float scale;                  // power of two that brings the centred data into fp16 range
     const int *shift_s;           // LDS: fixed-point shifts [32]
@@ -353,6 +356,9 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     asm volatile("" : "+v"(mask));                  // keep the mask in a VGPR
 
     const bool any_wide = c.wide_s[32] != 0;
+    // this lane's copy of the accumulators
+    unsigned long long *const sums_l = c.sums + (lane & (c.copies - 1)) * c.real_rows * (DP + 1);
+    int *const cnts_l = c.cnts + (lane & (c.copies - 1)) * c.real_rows;
 
     // Raw features of this lane's half of its points.  The rows of the next step are loaded while this step
     // runs: the loads are unconditional (addresses clamped into the chunk and the row, masking happens when the
@@ -669,10 +675,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                             if (hl != oh) nl = nlo;
                             const int rowbase = r * c.k0 + r * (r - 1) / 2;
                             if (pvalid) {
-                                unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+                                unsigned long long *sn = sums_l + (rowbase + nl) * (DP + 1) + f0;
 #pragma unroll
                                 for (int s = 0; s < H; ++s) atomicAdd(sn + s, (unsigned long long)fx[pb][s]);
-                                if (hl == 0) atomicAdd(&c.cnts[rowbase + nl], 1);
+                                if (hl == 0) atomicAdd(&cnts_l[rowbase + nl], 1);
                                 if (any_wide) add_low(p, rowbase, 0xff, nl);
                             }
                         }
@@ -692,7 +698,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     const int r = S == 8 ? 0 : oh * ST + st;
                     const int rowbase = r * c.k0 + r * (r - 1) / 2;
                     if (act) {
-                        unsigned long long *sn = c.sums + (rowbase + nl) * (DP + 1) + f0;
+                        unsigned long long *sn = sums_l + (rowbase + nl) * (DP + 1) + f0;
                         long long v[H];
 #pragma unroll
                         for (int s = 0; s < H; ++s) {
@@ -702,12 +708,12 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                                 if (pb == q) v[s] = fx[q][s];
                             atomicAdd(sn + s, (unsigned long long)v[s]);
                         }
-                        if (hl == 0) atomicAdd(&c.cnts[rowbase + nl], 1);
+                        if (hl == 0) atomicAdd(&cnts_l[rowbase + nl], 1);
                         if (ol != 0xff) {   // 0xff: no label yet, nothing to take back
-                            unsigned long long *so = c.sums + (rowbase + ol) * (DP + 1) + f0;
+                            unsigned long long *so = sums_l + (rowbase + ol) * (DP + 1) + f0;
 #pragma unroll
                             for (int s = 0; s < H; ++s) atomicAdd(so + s, (unsigned long long)(-v[s]));
-                            if (hl == 0) atomicAdd(&c.cnts[rowbase + ol], -1);
+                            if (hl == 0) atomicAdd(&cnts_l[rowbase + ol], -1);
                         }
                         if (any_wide) add_low(base + pb * 32 + n, rowbase, ol, nl);
                     }
@@ -799,7 +805,8 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     const int k0 = plan.k_min + g.run0;                                   // k of the group's first run
     const int grow0 = rows_before(plan.k_min, g.run0);                    // first centroid row of the group
     const int real_rows = rows_before(plan.k_min, g.run0 + g.n_runs) - grow0;
-    const Carve cv = carve_lds(DP, d, g.n_tiles, real_rows);
+    const int copies = g.copies;
+    const Carve cv = carve_lds(DP, d, g.n_tiles, real_rows, copies);
 
     uint4 *opA_s = reinterpret_cast<uint4 *>(smem + cv.opA);
     float *cs_lds = reinterpret_cast<float *>(smem + cv.cs);
@@ -836,8 +843,8 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
         if (tid == 0) *next_slab = WV;
         if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
         if (!FINAL) {
-            for (int e = tid; e < real_rows * (DP + 1); e += TH) sums[e] = 0ull;
-            for (int e = tid; e < real_rows; e += TH) cnts[e] = 0;
+            for (int e = tid; e < copies * real_rows * (DP + 1); e += TH) sums[e] = 0ull;
+            for (int e = tid; e < copies * real_rows; e += TH) cnts[e] = 0;
         }
     }
     __syncthreads();
@@ -846,7 +853,7 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     c.opA_s = opA_s;
     c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
     c.next_slab = next_slab;
-    c.sums = sums; c.cnts = cnts; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
+    c.sums = sums; c.cnts = cnts; c.copies = copies; c.real_rows = real_rows; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
     c.scale = *reinterpret_cast<const float *>(wsb + a.off_colinfo + kColScaleOff);
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
     c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
@@ -893,9 +900,17 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     if (!FINAL) {
         unsigned long long *psum = reinterpret_cast<unsigned long long *>(wsb + a.off_psum) +
                                    ((int64_t)chunk * plan.total_rows + grow0) * d;
-        for (int e = tid; e < real_rows * d; e += TH) psum[e] = sums[(e / d) * (DP + 1) + e % d];
+        for (int e = tid; e < real_rows * d; e += TH) {
+            unsigned long long v = 0ull;
+            for (int cp = 0; cp < copies; ++cp) v += sums[(cp * real_rows + e / d) * (DP + 1) + e % d];
+            psum[e] = v;
+        }
         int *pcnt = reinterpret_cast<int *>(wsb + a.off_pcnt) + (int64_t)chunk * plan.total_rows + grow0;
-        for (int e = tid; e < real_rows; e += TH) pcnt[e] = cnts[e];
+        for (int e = tid; e < real_rows; e += TH) {
+            int v = 0;
+            for (int cp = 0; cp < copies; ++cp) v += cnts[cp * real_rows + e];
+            pcnt[e] = v;
+        }
     }
     if (FINAL || TRACE) {
         if (tid < g.n_runs) {
@@ -1343,7 +1358,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     for (int gi = 0; gi < plan.n_groups; ++gi) {
         const GroupDesc &g = plan.g[gi];
         const int rr = rows_before(plan.k_min, g.run0 + g.n_runs) - rows_before(plan.k_min, g.run0);
-        const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr).total;
+        const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr, g.copies).total;
         if (need > lds) lds = need;
     }
     const dim3 grid(plan.n_groups * plan.n_chunks, batch);
@@ -1386,9 +1401,9 @@ LloydGeometry lloyd_geometry(int dp)
     return g;
 }
 
-int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows)
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, int copies)
 {
-    return carve_lds(dp, d, n_tiles, real_rows).total;
+    return carve_lds(dp, d, n_tiles, real_rows, copies).total;
 }
 
 constexpr int kFillWorkgroups = 256;   // one per compute unit
@@ -1416,7 +1431,7 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
             const int n_tiles = (quads + S - 1) / S;
             const int real_rows = rows_before(k_min, run + nr) - rows_before(k_min, run);
             if (n_tiles > 32) continue;
-            if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows) > geo.lds_budget) continue;
+            if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows, 1) > geo.lds_budget) continue;
             // cost per real row: padded rows and a fixed per-group overhead
             const double score = (n_tiles * 32.0 + 24.0) / real_rows;
             if (score < best_score - 1e-12) {
@@ -1426,7 +1441,16 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
         if (best_R == 0 || plan->n_groups >= kMaxGroups) return RLS_ERR_INVALID_ARG;
         GroupDesc &g = plan->g[plan->n_groups++];
         g.run0 = (int16_t)run; g.n_runs = (int16_t)best_nr; g.S = (int16_t)(8 / best_R); g.n_tiles = (int16_t)best_tiles;
-        g.pad0 = 0; g.pad = 0; g.tile0 = tiles;
+        g.pad = 0; g.tile0 = tiles;
+        // Runs with few clusters send many lanes of a wave to the same accumulator address (32 / k on average), which
+        // the LDS works off one after the other: such groups keep several copies of their accumulators, LDS permitting.
+        {
+            const int kmax_g = k_min + run + best_nr - 1;
+            const int real_rows = rows_before(k_min, run + best_nr) - rows_before(k_min, run);
+            int copies = kmax_g <= 8 ? 16 : (kmax_g <= 16 ? 8 : (kmax_g <= 32 ? 4 : (kmax_g <= 64 ? 2 : 1)));
+            while (copies > 1 && lloyd_group_lds_bytes(dp, d, best_tiles, real_rows, copies) > geo.lds_budget) copies >>= 1;
+            g.copies = (int16_t)copies;
+        }
         tiles += best_tiles;
         run += best_nr;
     }

@@ -34,7 +34,7 @@ struct GroupDesc {
     int16_t n_runs;    // real runs in this group (<= 8 / S)
     int16_t S;         // slots per run: 1, 2, 4 or 8
     int16_t n_tiles;   // 32-row tiles
-    int16_t pad0;
+    int16_t copies;    // copies of the LDS accumulators (a power of two up to 16)
     int16_t pad;
     int32_t tile0;     // tiles of all earlier groups (offset of this group's operand block)
 };
@@ -67,7 +67,7 @@ struct LloydGeometry {
 LloydGeometry lloyd_geometry(int dp);
 int padded_d(int d);
 // LDS bytes of a group: operand tiles + centroid copy + exact-sum accumulators + fixed part
-int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows);
+int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, int copies);
 // `batch`: spaces swept by the same launches (sizes the chunks so that the whole batch gives ~1024 workgroups)
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch, SweepPlan *plan);
 
