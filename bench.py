@@ -217,7 +217,11 @@ def main() -> int:
         # tree scoring: bound by LDS gathers and vector issue (T*D node visits per 4d+4 bytes), shown against HBM for scale
         "gbt_score": {"ms": score_ms, "node_visits_per_s": float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3),
                       "algorithmic_GBps": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9,
-                      "hbm_frac": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                      "hbm_frac": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      # the walk is bound by LDS: 12 bytes per lane and visit (node 8, feature value 4) against
+                      # 128 B/clk on each of 256 CUs at 2.4 GHz
+                      "lds_GBps": 12.0 * float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3) / 1e9,
+                      "lds_frac": 12.0 * float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3) / (256 * 128 * 2.4e9)},
     }
 
     if not batched and not args.no_early_exit:
