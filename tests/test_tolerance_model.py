@@ -1,0 +1,49 @@
+"""The Lloyd step kernel computes distances from two fp16 pieces per operand and re-decides every comparison that falls
+inside an error bound with the exact arithmetic.  The part of that bound that covers what the pieces leave out is
+checked here on the CPU against a model of the split (numpy only; no GPU, no oracle): per distance at most
+24.5 * 2^-23 * (|x'|^2 + |c'|^2) plus 0.0781 * d for pieces below 2^-14 that may be lost altogether
+(comment at `eps_a` in paper_1905_12799_amd/csrc/kmeans_lloyd.hip)."""
+import numpy as np
+import pytest
+
+
+def rtz16(v):
+    """fp32 -> fp16 rounded toward zero (as the packed conversion the kernel uses), returned as fp32."""
+    h = v.astype(np.float16)
+    away = np.abs(h.astype(np.float32)) > np.abs(v)
+    return np.where(away, np.nextafter(h, np.float16(0)), h).astype(np.float32)
+
+
+def lost_below_normal(v):
+    return np.where(np.abs(v) < 2.0 ** -14, 0.0, v).astype(np.float32)
+
+
+@pytest.mark.parametrize("flush", [False, True])
+def test_two_piece_products_stay_inside_the_bound(flush):
+    rng = np.random.default_rng(5 + int(flush))
+    worst = 0.0
+    for trial in range(80):
+        d = int(rng.choice([8, 16, 32]))
+        n = 2048
+        scale = 2.0 ** rng.integers(-24, 14)
+        x = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+        c = (rng.standard_normal((n, d)) * scale * rng.choice([1.0, 0.01, 30.0])).astype(np.float32)
+        if trial % 3 == 0:                       # one column much larger than the rest
+            x[:, 0] *= 2.0 ** 10
+            c[:, 0] *= 2.0 ** 10
+        x = np.clip(x, -2.0 ** 13, 2.0 ** 13)    # the kernel's scaling keeps |x'| < 2^13, |2c'| < 2^14
+        c = np.clip(c, -2.0 ** 13, 2.0 ** 13)
+        C = (-2.0 * c).astype(np.float32)
+        xh, Ch = rtz16(x), rtz16(C)
+        xl, Cl = rtz16(x - xh), rtz16(C - Ch)
+        assert np.all((x - xh).astype(np.float64) == x.astype(np.float64) - xh.astype(np.float64))   # remainder is exact in fp32
+        if flush:
+            xh, xl, Ch, Cl = (lost_below_normal(a) for a in (xh, xl, Ch, Cl))
+        f64 = np.float64
+        approx = (xh.astype(f64) * Ch + xh.astype(f64) * Cl + xl.astype(f64) * Ch).sum(1)
+        exact = (x.astype(f64) * C.astype(f64)).sum(1)
+        S = (x.astype(f64) ** 2).sum(1) + (c.astype(f64) ** 2).sum(1)
+        bound = 24.5 * 2.0 ** -23 * S + 0.0781 * d + d * 2.0 ** -27
+        worst = max(worst, float((np.abs(approx - exact) / bound).max()))
+    assert worst <= 1.0
+    assert worst > 0.01      # the model is exercised: the errors are not orders of magnitude below the bound
