@@ -871,7 +871,8 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     // norms d_pad 2^-24 S each; centring 2 2^-23 S: 54.5 2^-23 S at d_pad <= 16 and 77.5 2^-23 S at 32.  Twice that
     // is 109 and 155; the bound used is 120 and 200.  A piece below 2^-14 (an fp16 subnormal) is counted as lost
     // altogether: per distance at most 2^-14 sqrt(d) (|x'| + |2c'|) <= 2^-24 S + 0.078 d, hence the absolute term
-    // kTolFloor next to the relative one (the 2^-24 S makes the 24 above 24.5).
+    // kTolFloor next to the relative one (the 2^-24 S makes the 24 above 24.5).  (Measured on gfx950: one MFMA of this
+    // shape is within 1.9 2^-24 of the sum of the magnitudes of its terms, against the five roundings charged.)
     c.eps_a = (float)(5 * ((DP < 16 ? 16 : DP) + 8)) * 1.1920928955078125e-07f;   // 5 (max(DP, 16) + 8) 2^-23
 
     double jloc[8];
