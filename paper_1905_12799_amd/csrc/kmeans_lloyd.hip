@@ -420,7 +420,15 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     // LDS, so the waves of the workgroup finish together however their close calls and updates are spread.
     constexpr int SLAB = SLAB_;
     const int n_slabs = (int)((c.chunk_end - c.chunk_begin + SLAB - 1) / SLAB);
+    // (a pass that sums the loss hands its slabs out in a fixed order instead - wave w takes slabs w, w + waves, ... -
+    // so that the fp64 partial sums of a wave, and with them the reported loss, are the same in every run)
+    int fixed_next = wave;
+    const int n_waves = (int)(blockDim.x >> 6);
     auto grab = [&]() -> int {
+        if (LOSS) {
+            fixed_next += n_waves;
+            return fixed_next;
+        }
         int v = 0;
         if (lane == 0) v = atomicAdd(c.next_slab, 1);
         return __builtin_amdgcn_readfirstlane(v);

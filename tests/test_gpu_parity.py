@@ -482,6 +482,50 @@ def test_sweep_until_knee_equals_full_sweep_and_oracle(rls, orc, name, N, k_min,
     np.testing.assert_array_equal(part.labels[:n_done].cpu().numpy(), ref["labels"][:n_done])
 
 
+def test_sweep_is_reproducible_run_to_run(rls):
+    """Labels and centroids are exact; the fp64 loss sums are taken in a fixed order: two runs agree bit for bit."""
+    p = synth.make_problem(synth.WORKLOADS["mid"], N=30011)
+    Xd = dev(p.X)
+    a = rls.kmeans_sweep(Xd, 1, 40, 5, seed=9, want_trace=True)
+    b = rls.kmeans_sweep(Xd, 1, 40, 5, seed=9, want_trace=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a.labels, b.labels) and torch.equal(a.centroids, b.centroids)
+    assert torch.equal(a.inertia, b.inertia) and torch.equal(a.trace, b.trace)
+
+
+def test_sweep_graph_capture_and_replay(rls):
+    """A caller can record a whole sweep into a HIP graph (the sweep enqueues kernels only: no allocation, no host
+    synchronisation, no memset nodes) and replay it; every replay, with eager work in between, gives the eager result."""
+    p = synth.make_problem(synth.WORKLOADS["tiny"])
+    Xd = dev(p.X)
+    k_min, k_max, iters = 1, 16, 6
+    ws = torch.empty(rls.kmeans_sweep_workspace_bytes(Xd.shape[0], Xd.shape[1], k_min, k_max, 1) + 256, dtype=torch.uint8, device="cuda")
+    init = rls.kmeanspp_chain(Xd, k_max, 5)
+    eager = rls.kmeans_sweep(Xd, k_min, k_max, iters, init_idx=init, workspace=ws, check_status=False)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (eager.labels, eager.centroids, eager.inertia)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        rls.kmeans_sweep(Xd, k_min, k_max, iters, init_idx=init, workspace=ws, check_status=False)   # warm-up on this stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            res = rls.kmeans_sweep(Xd, k_min, k_max, iters, init_idx=init, workspace=ws, check_status=False)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (res.labels, res.centroids, res.inertia):
+            t.zero_()
+        other = rls.kmeans_sweep(Xd, 2, 5, 2, seed=rep)        # eager work in between, with its own workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(res.status.item()) == 0
+        for got, exp in zip((res.labels, res.centroids, res.inertia), want):
+            assert torch.equal(got, exp), f"replay {rep}"
+        assert other.inertia.shape[0] == 4
+
+
 def test_sweep_status_flags(rls):
     X = np.ones((600, 8), dtype=np.float32)
     X[5, 2] = np.inf
