@@ -21,7 +21,11 @@
  *     through `workspace_dev`, sized by the matching *_workspace_bytes query.
  *   - `stream` is a hipStream_t passed as void*.  Calls enqueue kernels on it and return
  *     without synchronising; outputs are valid once the stream has drained.  The one exception,
- *     rls_kmeans_sweep_until_knee, says so.
+ *     rls_kmeans_sweep_until_knee, says so.  Such a call may be recorded into a HIP graph by the
+ *     caller (kernels only: nothing is allocated, copied to the host or cleared with a memset node;
+ *     call it once outside the capture first, which sets the kernels' launch attributes).
+ *   - Results do not depend on the run: labels, centroids, configurations and scores are exact or
+ *     summed in a fixed order, and so are the reported losses.
  *   - Matrices are row-major fp32 with an explicit leading dimension in elements.
  *   - Argument errors are detected on the host before anything is enqueued.  Conditions that
  *     only the data can reveal (see rls_kmeans_sweep) are reported through `status_dev`.
