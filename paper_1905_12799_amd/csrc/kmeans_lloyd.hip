@@ -720,7 +720,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                         if (ol != 0xff) {   // 0xff: no label yet, nothing to take back
                             unsigned long long *so = sums_l + (rowbase + ol) * (DP + 1) + f0;
 #pragma unroll
-                            for (int s = 0; s < H; ++s) atomicAdd(so + s, (unsigned long long)(-v[s]));
+                            for (int s = 0; s < H; ++s)
+                                __hip_atomic_fetch_sub(so + s, (unsigned long long)v[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                             if (hl == 0) atomicAdd(&cnts_l[rowbase + ol], -1);
                         }
                         if (any_wide) add_low(base + pb * 32 + n, rowbase, ol, nl);
