@@ -45,6 +45,7 @@ def main() -> int:
     ap.add_argument("--serial-score", action="store_true",
                     help="score on the main stream before the sweep instead of beside it on a second stream")
     ap.add_argument("--no-early-exit", action="store_true", help="skip the extra timing of the sweep with early exit at the knee")
+    ap.add_argument("--no-per-k", action="store_true", help="skip the extra timing of the Lloyd step for single values of k")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -236,6 +237,26 @@ def main() -> int:
                                                          want_labels=want_labels)
         torch.cuda.synchronize()
         out["early_exit"] = {"ms": (time.perf_counter() - t2) * 1e3 / 3, "chosen_k": k_e, "k_computed": n_done, "k_wave": 8}
+
+    if not batched and not args.no_per_k:
+        # The Lloyd step for one k at a time (outside the timed steps): where the launch time leaves the floor set by
+        # reading the trajectory and starts to follow the distance work.  Same kernel, a plan with a single run.
+        per_k = []
+        for k in [k for k in (1, 2, 4, 8, 16, 32, 64, 128) if w.k_min <= k <= w.k_max]:
+            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False)
+            torch.cuda.synchronize()
+            rls.profile_enable(True)
+            rls.profile_read()
+            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False)
+            n_l, ms_l = rls.profile_read()
+            rls.profile_enable(False)
+            t_l = ms_l / max(n_l, 1) * 1e-3
+            flops_k = 2.0 * (3.0 * max(d_pad, 16) + 16.0) * max(k, 32) * w.N       # issued: tiles of 32 centroids
+            per_k.append({"k": k, "launch_ms": t_l * 1e3, "config_iter_per_s": w.N / t_l,
+                          "hbm_frac": 4.0 * w.d * w.N / t_l / 1e9 / HBM_PEAK_GBS,
+                          "algorithmic_TFLOPs": 2.0 * w.d * k * w.N / t_l / 1e12,
+                          "mfma_f16_frac": flops_k / t_l / 1e12 / MFMA_F16_PEAK_TFLOPS})
+        out["lloyd_step_per_k"] = per_k
 
     if not args.no_cpu_baseline:
         import oracle

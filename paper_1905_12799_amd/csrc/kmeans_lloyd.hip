@@ -388,7 +388,11 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             if (c.vec_x) {
 #pragma unroll
                 for (int c4 = 0; c4 < H / 4; ++c4) {
-                    const float4 v = *reinterpret_cast<const float4 *>(Xs + (ro + foff[4 * c4]));
+                    // the offset is made opaque: otherwise the compiler merges this branch with the one below into
+                    // four 4-byte loads per 16 bytes, and a wave's rows then cost four times the cache look-ups
+                    unsigned off = ro + foff[4 * c4];
+                    asm volatile("" : "+v"(off));
+                    const float4 v = *reinterpret_cast<const float4 *>(Xs + off);
                     xnext[pb][4 * c4 + 0] = v.x; xnext[pb][4 * c4 + 1] = v.y; xnext[pb][4 * c4 + 2] = v.z; xnext[pb][4 * c4 + 3] = v.w;
                 }
             } else {
@@ -1430,7 +1434,8 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
     int run = 0;
     while (run < plan->n_runs) {
         // candidates: R runs side by side (8 / R slots each); take the one with the least padding per real
-        // row, preferring the larger R
+        // row, preferring the larger R - except between candidates that cover the same runs at the same padding
+        // (the end of a range, a single k): there the smaller R wins, since a lane keeps state for R runs, used or not
         int best_R = 0, best_tiles = 0, best_nr = 0;
         double best_score = 1e30;
         for (int R = 8; R >= 1; R >>= 1) {
@@ -1444,7 +1449,7 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
             if (lloyd_group_lds_bytes(dp, d, n_tiles, real_rows, 1) > geo.lds_budget) continue;
             // cost per real row: padded rows and a fixed per-group overhead
             const double score = (n_tiles * 32.0 + 24.0) / real_rows;
-            if (score < best_score - 1e-12) {
+            if (score < best_score - 1e-12 || (nr == best_nr && score < best_score + 1e-12)) {
                 best_score = score; best_R = R; best_tiles = n_tiles; best_nr = nr;
             }
         }
