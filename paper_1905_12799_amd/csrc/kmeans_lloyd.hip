@@ -329,7 +329,10 @@ struct WaveCtx {
     float eps_a;
 };
 
-template <int DP, int S, bool FINAL, bool TRACE>
+// VEC: rows of X may be read 16 bytes at a time.  A template parameter and not a run-time branch: with both load
+// paths in one function the compiler merges them into 4-byte loads, and a wave's rows then cost four times the
+// cache look-ups (which bounds sweeps over few k).
+template <int DP, int S, bool FINAL, bool TRACE, bool VEC>
 __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 {
     constexpr int NB = slab_blocks_of(DP, S);       // blocks of 32 points per wave and slab
@@ -369,7 +372,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     const unsigned ldx32 = (unsigned)c.ldx;          // checked on the host: 64 rows of ldx floats fit 32 bits
     unsigned foff[H];                                // this lane's clamped feature offsets (fixed for the launch)
 #pragma unroll
-    for (int s = 0; s < H; ++s) foff[s] = (unsigned)(c.vec_x ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1));
+    for (int s = 0; s < H; ++s) foff[s] = (unsigned)(VEC ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1));
     int oldn[NB][ST];                                // previous labels of the slab being fetched
     unsigned run_off[ST];                            // offset of this lane's runs in the label arrays (runs are N apart)
 #pragma unroll
@@ -385,14 +388,10 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         for (int pb = 0; pb < NB; ++pb) {
             const unsigned li = min((unsigned)(pb * 32 + n), last);
             const unsigned ro = li * ldx32;
-            if (c.vec_x) {
+            if (VEC) {
 #pragma unroll
                 for (int c4 = 0; c4 < H / 4; ++c4) {
-                    // the offset is made opaque: otherwise the compiler merges this branch with the one below into
-                    // four 4-byte loads per 16 bytes, and a wave's rows then cost four times the cache look-ups
-                    unsigned off = ro + foff[4 * c4];
-                    asm volatile("" : "+v"(off));
-                    const float4 v = *reinterpret_cast<const float4 *>(Xs + off);
+                    const float4 v = *reinterpret_cast<const float4 *>(Xs + (ro + foff[4 * c4]));
                     xnext[pb][4 * c4 + 0] = v.x; xnext[pb][4 * c4 + 1] = v.y; xnext[pb][4 * c4 + 2] = v.z; xnext[pb][4 * c4 + 3] = v.w;
                 }
             } else {
@@ -802,6 +801,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     }
 }
 
+template <int DP, bool FINAL, bool TRACE, bool VEC>
+__device__ inline void wave_loop_of(int S, const WaveCtx &c, double (&jloc)[8])
+{
+    switch (S) {
+    case 1: wave_loop<DP, 1, FINAL, TRACE, VEC>(c, jloc); break;
+    case 2: wave_loop<DP, 2, FINAL, TRACE, VEC>(c, jloc); break;
+    case 4: wave_loop<DP, 4, FINAL, TRACE, VEC>(c, jloc); break;
+    default: wave_loop<DP, 8, FINAL, TRACE, VEC>(c, jloc); break;
+    }
+}
+
 template <int DP, bool FINAL, bool TRACE>
 __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPlan plan, StepArgs a)
 {
@@ -892,11 +902,9 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
 #pragma unroll
     for (int i = 0; i < 8; ++i) jloc[i] = 0.0;
 
-    if (c.chunk_begin < c.chunk_end) switch (g.S) {
-    case 1: wave_loop<DP, 1, FINAL, TRACE>(c, jloc); break;
-    case 2: wave_loop<DP, 2, FINAL, TRACE>(c, jloc); break;
-    case 4: wave_loop<DP, 4, FINAL, TRACE>(c, jloc); break;
-    default: wave_loop<DP, 8, FINAL, TRACE>(c, jloc); break;
+    if (c.chunk_begin < c.chunk_end) {
+        if (c.vec_x) wave_loop_of<DP, FINAL, TRACE, true>(g.S, c, jloc);
+        else wave_loop_of<DP, FINAL, TRACE, false>(g.S, c, jloc);
     }
 
     if (FINAL || TRACE) {

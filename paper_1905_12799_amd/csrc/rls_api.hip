@@ -61,7 +61,7 @@ using namespace rls;
 
 extern "C" {
 
-int32_t rls_version(void) { return 108; }
+int32_t rls_version(void) { return 109; }
 
 const char *rls_error_string(int32_t code)
 {
