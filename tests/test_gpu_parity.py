@@ -287,6 +287,20 @@ def test_sweep_shapes(rls, orc, N, d, k_min, k_max, iters):
     compare_sweep(orc, X, res, ref, k_min, k_max)
 
 
+@pytest.mark.parametrize("d", [5, 16, 32])
+@pytest.mark.parametrize("k_min,k_max", [(1, 1), (3, 3), (8, 8), (31, 31), (32, 32), (33, 33), (64, 64), (100, 100),
+                                         (128, 128), (30, 33), (62, 64), (127, 128)])
+def test_sweep_single_k_and_narrow_ranges(rls, orc, d, k_min, k_max):
+    # a sweep over one k (plain k-means) or the last few k of a range: one run per group, or a group that is not full
+    rng = np.random.default_rng(1000 * d + 7 * k_min + k_max)
+    N = 2100
+    centres = rng.uniform(-15, 15, size=(11, d))
+    X = (centres[rng.integers(0, 11, size=N)] + rng.standard_normal((N, d))).astype(np.float32)
+    X[::7] = np.round(X[::7])                       # some exact ties
+    res, ref = run_both(rls, orc, X, k_min, k_max, 3, seed=k_min + d)
+    compare_sweep(orc, X, res, ref, k_min, k_max)
+
+
 def test_sweep_integer_ties_and_duplicates(rls, orc):
     # small-integer data with many duplicate rows: exact distance ties everywhere; lowest index must win
     rng = np.random.default_rng(3)
