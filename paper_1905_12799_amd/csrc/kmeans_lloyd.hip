@@ -1008,14 +1008,22 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     int shift = 0, wide = 0, msb = -(1 << 20);
     if (l < d) {
         ColPart t = part[l];
-        for (int g = 1; g < n_blocks; ++g) {
-            const ColPart o = part[g * 32 + l];
-            t.sum = __dadd_rn(t.sum, o.sum);
-            t.min_lsb = min(t.min_lsb, o.min_lsb);
-            t.max_msb = max(t.max_msb, o.max_msb);
-            t.bad |= o.bad;
-            t.vmin = fminf(t.vmin, o.vmin);
-            t.vmax = fmaxf(t.vmax, o.vmax);
+        // four partial results in flight at a time (the walk is bound by their latency); the sums keep the block order
+        constexpr int U = 4;
+        for (int g0 = 1; g0 < n_blocks; g0 += U) {
+            ColPart o[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) o[u] = part[min(g0 + u, n_blocks - 1) * 32 + l];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (g0 + u >= n_blocks) continue;
+                t.sum = __dadd_rn(t.sum, o[u].sum);
+                t.min_lsb = min(t.min_lsb, o[u].min_lsb);
+                t.max_msb = max(t.max_msb, o[u].max_msb);
+                t.bad |= o[u].bad;
+                t.vmin = fminf(t.vmin, o[u].vmin);
+                t.vmax = fmaxf(t.vmax, o[u].vmax);
+            }
         }
         if (t.bad) atomicOr(&flags, RLS_STATUS_NONFINITE);
         else {
@@ -1325,7 +1333,16 @@ __global__ void lloyd_loss_kernel(int n_runs, int n_chunks, const int32_t *statu
     if (r >= n_runs || status[b] != 0) return;
     const double *pj = reinterpret_cast<const double *>(ws + (int64_t)b * ws_bs + off_pj);
     double v = 0.0;
-    for (int c = 0; c < n_chunks; ++c) v = __dadd_rn(v, pj[(int64_t)c * n_runs + r]);
+    // eight loads in flight at a time (the walk is bound by their latency); the additions keep the chunk order
+    constexpr int U = 8;
+    for (int c0 = 0; c0 < n_chunks; c0 += U) {
+        double t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) t[u] = pj[(int64_t)min(c0 + u, n_chunks - 1) * n_runs + r];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (c0 + u < n_chunks) v = __dadd_rn(v, t[u]);
+    }
     out[(int64_t)b * out_bs + (int64_t)r * out_stride + out_off] = v;
 }
 
