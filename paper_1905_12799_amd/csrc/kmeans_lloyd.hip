@@ -46,9 +46,9 @@ constexpr int kColScaleOff = 400;             // byte offset of the scale factor
 __host__ __device__ constexpr int tile_points_of(int dp) { return dp == 32 ? 256 : 512; }
 // 32-point blocks a wave takes per slab.  Up to d_pad = 16: one, which keeps a wave under 168 registers so that three
 // waves fit a SIMD (measured: 6% shorter launches than two waves with two blocks each).  At d_pad = 32 three waves do
-// not fit; there a wave takes two blocks, except with many runs side by side, where the best keys of 4 runs x 2 blocks
+// not fit; there a wave takes two blocks, except with eight runs side by side, where the best keys of 4 runs x 2 blocks
 // would not fit the registers next to the operands.
-__host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp <= 16 ? 1 : (s < 4 ? 1 : 2); }
+__host__ __device__ constexpr int slab_blocks_of(int dp, int s) { return dp <= 16 ? 1 : (s < 2 ? 1 : 2); }
 // threads of a step workgroup: up to d_pad = 16 one block per slab leaves room for three waves per SIMD
 __host__ __device__ constexpr int step_threads_of(int dp) { return dp <= 16 ? 768 : 512; }
 // MFMA operands: a lane holds 8 fp16 values of its half of the features per K-step (v_mfma_f32_32x32x16_f16);

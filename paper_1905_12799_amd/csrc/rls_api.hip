@@ -61,7 +61,7 @@ using namespace rls;
 
 extern "C" {
 
-int32_t rls_version(void) { return 109; }
+int32_t rls_version(void) { return 110; }
 
 const char *rls_error_string(int32_t code)
 {
