@@ -10,7 +10,9 @@ N x (number of k) x (Lloyd rounds) per step divided by the step time.
 
 Prints ONE JSON line.  `roofline` describes the dominant kernel (the fused assign + update Lloyd step),
 timed with HIP events recorded by the library on the launch stream during the timed steps;
-`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.  Outside the timed steps the
+line also carries `early_exit` (the sweep that stops at the knee) and `lloyd_step_per_k` (the Lloyd step of a
+sweep over one k at a time: launch time, points per second, fractions of the HBM and fp16 matrix peaks).
 """
 import argparse
 import json
