@@ -94,6 +94,14 @@ def kmeanspp_chain(X, k_max: int, seed: int) -> np.ndarray:
     return idx
 
 
+def draw_index(D, r: float) -> int:
+    """The D^2 draw of the seeding chain on a given distance array: first index whose prefix sum exceeds r."""
+    D = np.ascontiguousarray(D, dtype=np.float64)
+    fn = lib().orc_draw_index
+    fn.restype = ctypes.c_int64
+    return int(fn(_p(D), ctypes.c_int64(D.shape[0]), ctypes.c_double(r)))
+
+
 def lloyd(X, k: int, iters: int, init_idx, want_trace: bool = False):
     """One k. Returns (labels int32 [N], centroids fp32 [k,d], inertia, half-step trace [2*iters+1] or None)."""
     X = _f32(X)

@@ -20,7 +20,9 @@
  * and +-inf thresholds; the seeding draw against its D^2 law, SplitMix64 test
  * vectors and the prefix property; Lloyd against brute force over all
  * labelings, monotone loss over every half step, planted clusters, closed
- * forms for k = 1 and k = N, exact means via rationals; the knee rule against
+ * forms for k = 1 and k = N, exact means via rationals; the draw's boundary
+ * branch and the two-nearest helper of the parity tests against NumPy brute
+ * force; the knee rule against
  * hand-made curves following Algorithm 1; snapping against brute force.
  * The whole chain has no numeric example in the paper: parity unpinned against
  * the paper beyond those properties.
@@ -101,6 +103,22 @@ static double sqdist(const float *x, const float *c, int32_t d)
 }
 
 /* ------------------------------------------------------------------------ */
+/* The D^2 draw: the first index whose inclusive prefix sum of D (taken in   */
+/* index order) exceeds r.  When no prefix does - r was rounded up to the    */
+/* total - the last index with D > 0 is taken; -1 when no D is positive.     */
+int64_t orc_draw_index(const double *D, int64_t N, double r)
+{
+    double prefix = 0.0;
+    int64_t last_pos = -1;
+    for (int64_t i = 0; i < N; ++i) {
+        prefix = prefix + D[i];
+        if (D[i] > 0.0) last_pos = i;
+        if (prefix > r) return i;
+    }
+    return last_pos;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Seeding: one k-means++ chain (D^2 sampling) of k_max centres.  A run with */
 /* k clusters starts from the first k of them.  The paper does not say how   */
 /* k-means is initialised; the workload definition asks for k-means++.       */
@@ -123,15 +141,7 @@ int32_t orc_kmeanspp_chain(const float *X, int64_t N, int32_t d, int64_t ldx,
         }
         int64_t pick = -1;
         if (S > 0.0) {
-            const double r = orc_uniform(seed, (uint64_t)j) * S;
-            double prefix = 0.0;
-            int64_t last_pos = -1;
-            for (int64_t i = 0; i < N; ++i) {
-                prefix = prefix + D[i];
-                if (D[i] > 0.0) last_pos = i;
-                if (prefix > r) { pick = i; break; }
-            }
-            if (pick < 0) pick = last_pos; /* r rounded up to S */
+            pick = orc_draw_index(D, N, orc_uniform(seed, (uint64_t)j) * S);
         } else {
             /* every point coincides with a chosen centre: smallest index not chosen yet */
             for (int64_t i = 0; i < N && pick < 0; ++i) {

@@ -167,3 +167,57 @@ def test_sweep_matches_single_runs_and_packing(orc):
     # explicit initial indices reproduce the seeded sweep
     sw2 = orc.kmeans_sweep(p.X, 3, 7, 6, init_idx=chain)
     np.testing.assert_array_equal(sw2["centroids"], sw["centroids"])
+
+
+def seq_sqdist(x, c):
+    """Direct form in fp64, features in rising order, one rounding per operation (Python floats are fp64)."""
+    acc = 0.0
+    for a, b in zip(x.tolist(), c.tolist()):
+        diff = float(a) - float(b)
+        acc = acc + diff * diff
+    return acc
+
+
+def test_two_nearest_against_brute_force(orc):
+    """The helper behind the near-tie rule and the sampled-label checks of the GPU parity tests."""
+    rng = np.random.default_rng(31)
+    for _ in range(300):
+        d = int(rng.integers(1, 33))
+        k = int(rng.integers(1, 40))
+        kind = rng.integers(0, 3)
+        if kind == 0:
+            C = rng.standard_normal((k, d)).astype(np.float32)
+            x = rng.standard_normal(d).astype(np.float32)
+        elif kind == 1:                                             # small integers: exact ties are common
+            C = rng.integers(0, 3, size=(k, d)).astype(np.float32)
+            x = rng.integers(0, 3, size=d).astype(np.float32)
+        else:                                                       # duplicated centroids
+            C = rng.standard_normal((max(1, k // 3), d)).astype(np.float32)[rng.integers(0, max(1, k // 3), size=k)]
+            x = rng.standard_normal(d).astype(np.float32)
+        dist = np.array([seq_sqdist(x, C[j]) for j in range(k)])
+        d1, d2, arg = orc.two_nearest(x, C)
+        order = np.sort(dist)
+        assert d1 == order[0]
+        assert arg == int(np.argmin(dist))                          # first minimum: lowest index among ties
+        if k == 1:
+            assert d2 == np.inf
+        else:
+            assert d2 == order[1]                                   # a duplicate of the minimum counts as second
+    # the transposed operand and the dropped term fail: asymmetric case worked by hand
+    x = np.array([1.0, 2.0], dtype=np.float32)
+    C = np.array([[1.0, 5.0], [4.0, 2.0], [1.0, 2.5]], dtype=np.float32)
+    assert orc.two_nearest(x, C) == (0.25, 9.0, 2)
+
+
+def test_two_nearest_agrees_with_the_assignment_of_lloyd(orc):
+    """arg of the helper is the label Lloyd's assignment gives (zero rounds: assignment against the initial centres)."""
+    rng = np.random.default_rng(32)
+    X = np.round(rng.standard_normal((400, 6)) * 2).astype(np.float32)      # ties included
+    init = rng.choice(400, size=9, replace=False)
+    labels, C, J, _ = orc.lloyd(X, 9, 0, init)
+    total = 0.0
+    for i in range(400):
+        d1, _, arg = orc.two_nearest(X[i], C)
+        assert arg == labels[i]
+        total += d1
+    assert abs(total - J) <= 1e-12 * max(J, 1.0)

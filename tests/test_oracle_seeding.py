@@ -77,3 +77,25 @@ def test_all_points_coincide_fallback(orc):
     first = int(orc.uniform(seed, 0) * 5)
     rest = [i for i in range(5) if i != first][:3]
     assert got.tolist() == [first] + rest
+
+
+def test_draw_index_against_cumsum_and_boundary_branch(orc):
+    """The draw on its own: first prefix above r; r equal to (or above) the total takes the last positive entry."""
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        D = rng.integers(0, 5, size=n).astype(np.float64)          # integers: every prefix is exact
+        D[rng.random(n) < 0.3] = 0.0
+        total = D.sum()
+        if total == 0:
+            assert orc.draw_index(D, 0.0) == -1
+            continue
+        pre = np.cumsum(D)
+        for r in (0.0, 0.5, float(rng.uniform(0, total)), total - 0.5):
+            assert orc.draw_index(D, r) == int(np.argmax(pre > r))
+        last_pos = int(np.flatnonzero(D > 0)[-1])
+        assert orc.draw_index(D, total) == last_pos               # r rounded up to the total
+        assert orc.draw_index(D, total + 1.0) == last_pos
+    # an entry with D = 0 is never drawn: its prefix equals the one before it
+    D = np.array([0.0, 2.0, 0.0, 0.0, 3.0, 0.0])
+    assert [orc.draw_index(D, r) for r in (0.0, 1.9, 2.0, 4.9, 5.0)] == [1, 1, 4, 4, 4]
