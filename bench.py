@@ -8,11 +8,19 @@ the snap of the chosen centroids, the per-dimension mode of the trajectory and t
 that were visited before.  The headline value is config-iterations per second:
 N x (number of k) x (Lloyd rounds) per step divided by the step time.
 
-Prints ONE JSON line.  `roofline` describes the dominant kernel (the fused assign + update Lloyd step),
-timed with HIP events recorded by the library on the launch stream during the timed steps;
-`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.  Outside the timed steps the
-line also carries `early_exit` (the sweep that stops at the knee) and `lloyd_step_per_k` (the Lloyd step of a
-sweep over one k at a time: launch time, points per second, fractions of the HBM and fp16 matrix peaks).
+Prints ONE JSON line.  The top-level fields describe the headline workload (default: `large`, the 8M x 32
+configuration, the largest one a single GPU is asked to run), timed for exactly --steps steps after --warmup;
+`workloads` holds the same block for every workload of the run (default: the 1M x 16 `whole_layer` as well, with
+its own step counts stated inside).  Each block carries
+  roofline      the dominant kernel (the fused assign + update Lloyd step), timed with HIP events recorded by the
+                library on the launch stream during the timed steps.  Its contraction runs on the fp16 matrix
+                pipeline, so `frac` is the method's distance arithmetic (2 d k flop per point and (k, round)) over
+                the launch time over the dense fp16 MFMA peak; beside it the fraction of HBM peak the same launch
+                would need if every k read the trajectory on its own (`hbm_equivalent_frac`, can exceed 1: one read
+                serves up to eight k), the matrix work actually issued, and - from rocprofv3 counters of this
+                library version, else null - the HBM bytes really moved and the vector-issue utilisation
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload, with the scaling to the sweep's mix of k
+  lloyd_step_per_k / early_exit   extra timings outside the timed steps
 """
 import argparse
 import json
@@ -27,47 +35,39 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix (for scale: the fp32 contraction runs as fp16 pieces)
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix: the pipeline the distance tiles run on
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4.0   # wave64 vector instructions per second: 256 CUs x 4 SIMDs, one every 4 clocks
 
-# HBM bytes of one lloyd_step_kernel launch from rocprofv3 counters (profiles/lloyd_step_whole_layer_hbm_counters.md):
-# FETCH_SIZE / WRITE_SIZE in KiB per dispatch and the factors a plain 1 GiB copy gives for each counter.  Valid
-# only for the library version the counters were taken with; any other version reports traffic = null.
-HBM_COUNTERS = {
-    "whole_layer": {"version": 110, "fetch_kib": 169259.2, "write_kib": 59620.2, "fetch_scale": 2.0, "write_scale": 1.0},
+# rocprofv3 counters of one lloyd_step_kernel launch (mean over the rounds of a sweep), from the summaries under
+# profiles/ (lloyd_step_<workload>_hbm_counters.md: FETCH_SIZE / WRITE_SIZE in KiB per dispatch with the factors a
+# plain 1 GiB copy gives for each counter; lloyd_step_<workload>_sq_counters.md: SQ_INSTS_VALU).  Valid only for the
+# library version they were taken with; any other version reports null.
+COUNTERS = {
+    "whole_layer": {"version": 110, "fetch_kib": 169259.2, "write_kib": 59620.2, "fetch_scale": 2.0, "write_scale": 1.0,
+                    "valu_insts": 2.17e8},
 }
+DEFAULT_STEPS = {"tiny": (50, 5), "mid": (20, 5), "whole_layer": (10, 3), "large": (5, 2), "batched": (5, 2)}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="whole_layer", choices=["tiny", "mid", "whole_layer", "large", "batched"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
-    ap.add_argument("--serial-score", action="store_true",
-                    help="score on the main stream before the sweep instead of beside it on a second stream")
-    ap.add_argument("--no-early-exit", action="store_true", help="skip the extra timing of the sweep with early exit at the knee")
-    ap.add_argument("--no-per-k", action="store_true", help="skip the extra timing of the Lloyd step for single values of k")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
-        return 2
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
+
+def run_workload(name, steps, warmup, args):
+    """Times `steps` steps of workload `name` after `warmup`; returns its block of the JSON line."""
     import numpy as np
     import torch
 
     from paper_1905_12799_amd import binding as rls
     from paper_1905_12799_amd import synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    torch.cuda.set_device(0)
-    rls.lib()   # fails loudly when the HIP library is not built
-
-    w = synth.WORKLOADS[args.workload]
+    w = synth.WORKLOADS[name]
     batched = w.batch > 1
     if batched:
         probs = synth.make_batched_problems(w)
@@ -90,9 +90,9 @@ def main() -> int:
     hists = [torch.empty(dm.n_values, dtype=torch.int32, device="cuda") for dm in domains]
     want_labels = not args.no_labels
 
-    ev = {name: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for name in ("score", "sweep", "snap", "modes_visited")}
-    stage_ms = {name: 0.0 for name in ev}
+    ev = {n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for n in ("score", "sweep", "snap", "modes_visited")}
+    stage_ms = {n: 0.0 for n in ev}
 
     # Tree scoring and clustering both only read the trajectory: the scores are computed on a second stream (default
     # priority) beside the sweep, whose seeding chain is a string of short bandwidth-bound launches.
@@ -144,17 +144,17 @@ def main() -> int:
             main_stream.wait_stream(side_stream)
         if record:
             torch.cuda.synchronize()
-            for name in ev:
-                stage_ms[name] += ev[name][0].elapsed_time(ev[name][1])
+            for n in ev:
+                stage_ms[n] += ev[n][0].elapsed_time(ev[n][1])
         return chosen
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(False)
     torch.cuda.synchronize()
     rls.profile_enable(True)
     rls.profile_read()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         chosen = step(True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -166,65 +166,65 @@ def main() -> int:
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     point_iters = float(w.N) * B * n_k * w.iters
     value = point_iters / (ms_per_step * 1e-3)
-    sweep_ms = stage_ms["sweep"] / args.steps
-    score_ms = stage_ms["score"] / args.steps
+    sweep_ms = stage_ms["sweep"] / steps
+    score_ms = stage_ms["score"] / steps
 
-    # dominant kernel: the Lloyd step (assign + update for every k in one launch)
-    kernel_ms = kernel_ms_total / max(n_launch, 1)
+    # ---- dominant kernel: the Lloyd step (assign + update for every k in one launch) -------------------------
+    kernel_s = kernel_ms_total / max(n_launch, 1) * 1e-3
     sum_k = sum(range(w.k_min, w.k_max + 1))
-    alg_bytes = 4.0 * w.d * w.N * B * n_k                 # 4*d bytes per point and (k, round)
-    alg_flops = 2.0 * w.d * sum_k * w.N * B               # 2*d*k flops per point and (k, round)
-    gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
-    tflops = alg_flops / (kernel_ms * 1e-3) / 1e12
-    # The contraction is carried out on the fp16 matrix pipeline: per distance three products of fp16 pieces over the
-    # padded features plus one bias step of 16.  Which roofline is the higher floor for the algorithmic work?
+    alg_bytes = 4.0 * w.d * w.N * B * n_k                 # 4 d bytes per point and (k, round): every k reads the row
+    alg_flops = 2.0 * w.d * sum_k * w.N * B               # 2 d k flop per point and (k, round)
+    # matrix work as issued: per distance three products of fp16 pieces over the padded features plus one bias step of 16
     d_pad = 8 if w.d <= 8 else (16 if w.d <= 16 else 32)
-    mfma_flops = 2.0 * (3.0 * max(d_pad, 16) + 16.0) * sum_k * w.N * B
-    mfma_tflops = mfma_flops / (kernel_ms * 1e-3) / 1e12
-    hbm_time, mfma_time = alg_bytes / (HBM_PEAK_GBS * 1e9), mfma_flops / (MFMA_F16_PEAK_TFLOPS * 1e12)
-    if hbm_time >= mfma_time:
-        roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                    "traffic": None}
-    else:
-        roofline = {"bound": "mfma", "achieved": mfma_tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": mfma_tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None}
-    hc = HBM_COUNTERS.get(w.name)
+    issued_flops = 2.0 * (3.0 * max(d_pad, 16) + 16.0) * sum_k * w.N * B
+    tflops = alg_flops / kernel_s / 1e12
+    roofline = {
+        # The launch is bound by vector-instruction issue beside the matrix pipeline (the fold of the distance tiles
+        # into the two smallest keys per point), not by HBM: one read of a row serves up to eight k.  The fraction
+        # reported is that of the contraction's own peak, the dense fp16 MFMA rate.
+        "bound": "mfma", "dtype": "f16", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+        "kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_s * 1e3,
+        "algorithmic_flops_per_launch": alg_flops, "algorithmic_bytes_per_launch": alg_bytes,
+        "mfma_issued_frac": issued_flops / kernel_s / 1e12 / MFMA_F16_PEAK_TFLOPS,
+        "fp32_mfma_equivalent_frac": tflops / MFMA_F32_PEAK_TFLOPS,
+        "hbm_equivalent_GBps": alg_bytes / kernel_s / 1e9,
+        "hbm_equivalent_frac": alg_bytes / kernel_s / 1e9 / HBM_PEAK_GBS,
+        "hbm_traffic_frac": None, "valu_issue_frac": None,
+        "limiting_resource": "vector instruction issue (see valu_issue_frac when counters of this library version exist)",
+    }
+    hc = COUNTERS.get(w.name)
     if hc is not None and hc["version"] == rls.version() and want_labels:
         hbm_bytes = (hc["fetch_kib"] * hc["fetch_scale"] + hc["write_kib"] * hc["write_scale"]) * 1024.0
-        # same unit as `achieved` when the bound is HBM; the ratio to the algorithmic bytes is what matters
-        roofline["traffic"] = hbm_bytes / (kernel_ms * 1e-3) / 1e9
-        roofline["traffic_bytes_per_launch"] = hbm_bytes
-    roofline["algorithmic_bytes_per_launch"] = alg_bytes
-    roofline.update({"kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_ms,
-                     "algorithmic_GBps": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
-                     "algorithmic_TFLOPs": tflops, "fp32_mfma_equivalent_frac": tflops / MFMA_F32_PEAK_TFLOPS,
-                     "mfma_f16_TFLOPs": mfma_tflops, "mfma_f16_frac": mfma_tflops / MFMA_F16_PEAK_TFLOPS})
+        roofline["traffic"] = hbm_bytes                  # HBM bytes really moved per launch (rocprofv3 FETCH_SIZE, WRITE_SIZE)
+        roofline["hbm_traffic_frac"] = hbm_bytes / kernel_s / 1e9 / HBM_PEAK_GBS
+        roofline["valu_issue_frac"] = hc["valu_insts"] / kernel_s / VALU_ISSUE_PEAK
 
+    visits = float(w.N) * B * w.n_trees * w.depth
     out = {
-        "metric": "config_iter_per_s", "value": value, "unit": "config*iter/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "value": value, "ms_per_step": ms_per_step, "steps": steps, "warmup": warmup,
         "config": {"workload": f"{w.name}: N={w.N} d={w.d} batch={B} k={w.k_min}..{w.k_max} iters={w.iters} "
                                f"forest={w.n_trees}x{w.depth}", "labels_written": want_labels,
                    "knee_const": knee_const, "chosen_k": chosen[:4],
                    "score_stream": "main" if side_stream is None else "second stream beside the sweep"},
         "configs_scored_per_s": float(w.N) * B / (score_ms * 1e-3),
         "sweep_config_iter_per_s": point_iters / (sweep_ms * 1e-3),
-        "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / args.steps,
-                     "modes_visited": stage_ms["modes_visited"] / args.steps},
+        "stage_ms": {"gbt_score": score_ms, "kmeans_sweep": sweep_ms, "snap": stage_ms["snap"] / steps,
+                     "modes_visited": stage_ms["modes_visited"] / steps},
         "roofline": roofline,
         # tree scoring: bound by LDS gathers and vector issue (T*D node visits per 4d+4 bytes), shown against HBM for scale
-        "gbt_score": {"ms": score_ms, "node_visits_per_s": float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3),
+        "gbt_score": {"ms": score_ms, "node_visits_per_s": visits / (score_ms * 1e-3),
                       "algorithmic_GBps": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9,
                       "hbm_frac": (4.0 * w.d + 4.0) * w.N * B / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       # the walk is bound by LDS: 12 bytes per lane and visit (node 8, feature value 4) against
                       # 128 B/clk on each of 256 CUs at 2.4 GHz
-                      "lds_GBps": 12.0 * float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3) / 1e9,
-                      "lds_frac": 12.0 * float(w.N) * B * w.n_trees * w.depth / (score_ms * 1e-3) / (256 * 128 * 2.4e9)},
+                      "lds_GBps": 12.0 * visits / (score_ms * 1e-3) / 1e9,
+                      "lds_frac": 12.0 * visits / (score_ms * 1e-3) / (256 * 128 * 2.4e9)},
     }
 
     if not batched and not args.no_early_exit:
@@ -242,45 +242,145 @@ def main() -> int:
 
     if not batched and not args.no_per_k:
         # The Lloyd step for one k at a time (outside the timed steps): where the launch time leaves the floor set by
-        # reading the trajectory and starts to follow the distance work.  Same kernel, a plan with a single run.
+        # reading the trajectory and starts to follow the distance work.  Same kernel, a plan with a single run; here
+        # every launch reads the trajectory once for its one k, so the HBM fraction is a fraction.
         per_k = []
         for k in [k for k in (1, 2, 4, 8, 16, 32, 64, 128) if w.k_min <= k <= w.k_max]:
-            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False)
+            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False, workspace=ws)
             torch.cuda.synchronize()
             rls.profile_enable(True)
             rls.profile_read()
-            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False)
+            rls.kmeans_sweep(X, k, k, w.iters, seed=seeds[0], want_labels=False, workspace=ws)
             n_l, ms_l = rls.profile_read()
             rls.profile_enable(False)
             t_l = ms_l / max(n_l, 1) * 1e-3
             flops_k = 2.0 * (3.0 * max(d_pad, 16) + 16.0) * max(k, 32) * w.N       # issued: tiles of 32 centroids
             per_k.append({"k": k, "launch_ms": t_l * 1e3, "config_iter_per_s": w.N / t_l,
                           "hbm_frac": 4.0 * w.d * w.N / t_l / 1e9 / HBM_PEAK_GBS,
-                          "algorithmic_TFLOPs": 2.0 * w.d * k * w.N / t_l / 1e12,
-                          "mfma_f16_frac": flops_k / t_l / 1e12 / MFMA_F16_PEAK_TFLOPS})
+                          "mfma_f16_frac": 2.0 * w.d * k * w.N / t_l / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                          "mfma_issued_frac": flops_k / t_l / 1e12 / MFMA_F16_PEAK_TFLOPS})
         out["lloyd_step_per_k"] = per_k
 
+    del X, ws, scores, visited, forests
+    torch.cuda.empty_cache()
+
     if not args.no_cpu_baseline:
-        import oracle
-        p0 = probs[0]
-        ks = [k for k in (8, 32, 64, 128) if w.k_min <= k <= w.k_max] or [w.k_max]
-        iters_s = 20
-        chain = oracle.kmeanspp_chain(p0.X, max(ks), w.seed)
+        out["cpu_baseline"] = cpu_baseline(w, probs[0], value)
+    return out
+
+
+def cpu_baseline(w, p0, gpu_value):
+    """The oracle as it stands on the host cores, on a bounded sample of the workload: full N of one space, a few k,
+    a few Lloyd rounds (the cost of a round does not depend on which round it is: no early stop).  A round costs
+    a + b k per point (the exact update, one thread; the assignment, all threads), so the sample's rate is also
+    scaled to the sweep's own mix of k."""
+    import numpy as np
+
+    import oracle
+
+    ks = [k for k in (8, 32, 64, 128) if w.k_min <= k <= w.k_max] or [w.k_max]
+    if w.N * w.d > (1 << 27):
+        ks = [k for k in ks if k in (8, 64)] or ks[:1]          # 8M x 32: two k, a few rounds each
+    rounds = 4 if w.N * w.d > (1 << 27) else (16 if w.N >= (1 << 20) else 20)
+    rounds = min(rounds, max(w.iters, 1))
+    rng = np.random.default_rng(w.seed + 77)
+    init = rng.choice(w.N, size=max(ks), replace=False).astype(np.int64)      # seeded rows as initial centres
+    times = []
+    for k in ks:
         t = time.perf_counter()
-        for k in ks:
-            oracle.lloyd(p0.X, k, iters_s, chain)
-        dt = time.perf_counter() - t
-        n_s = min(w.N, 65536)
-        t = time.perf_counter()
-        oracle.gbt_score(p0.forest, p0.X[:n_s])
-        dt_s = time.perf_counter() - t
-        out["cpu_baseline"] = {
-            "value": float(w.N) * len(ks) * iters_s / dt, "unit": "config*iter/s", "cores": oracle.threads(),
-            "kind": "oracle",
-            "sample": f"Lloyd on the full N={w.N} of one space for k in {ks}, {iters_s} rounds each plus the final "
-                      f"assignment ({dt:.1f} s); tree scoring of the first {n_s} configurations on 1 thread ({dt_s:.1f} s)",
-            "configs_scored_per_s": n_s / dt_s,
-        }
+        oracle.lloyd(p0.X, k, rounds, init)
+        times.append(time.perf_counter() - t)
+    dt = sum(times)
+    # time of one run ~ (rounds + 1) assignments + rounds updates; per round and point: a + b k (least squares over the sample)
+    per_round = np.array(times) / (rounds + 0.5)
+    if len(ks) >= 2:
+        b_, a_ = np.polyfit(np.array(ks, dtype=np.float64), per_round, 1)
+    else:
+        b_, a_ = per_round[0] / ks[0], 0.0
+    a_, b_ = max(a_, 0.0), max(b_, 0.0)
+    n_k = w.k_max - w.k_min + 1
+    sweep_est = w.batch * sum((a_ + b_ * k) * (w.iters + 0.5) for k in range(w.k_min, w.k_max + 1))
+    est_value = float(w.N) * w.batch * n_k * w.iters / sweep_est if sweep_est > 0 else None
+    n_s = min(w.N, 65536)
+    t = time.perf_counter()
+    oracle.gbt_score(p0.forest, p0.X[:n_s])
+    dt_s = time.perf_counter() - t
+    return {
+        "value": float(w.N) * len(ks) * rounds / dt, "unit": "config*iter/s", "cores": oracle.threads(),
+        "cpu_model": cpu_model(), "kind": "oracle",
+        "sample": f"Lloyd on the full N={w.N} of one space for k in {ks}, {rounds} round(s) each plus the final "
+                  f"assignment ({dt:.1f} s), from seeded random rows as initial centres; tree scoring of the first "
+                  f"{n_s} configurations on 1 thread ({dt_s:.1f} s)",
+        "scaled_to_sweep": {"config_iter_per_s": est_value, "sweep_seconds_estimate": sweep_est,
+                            "model": "seconds per Lloyd round of one k = a + b*k, fitted to the sample; sweep = "
+                                     "(rounds + 1/2) * sum over k of (a + b*k) * spaces",
+                            "a": a_, "b": b_, "gpu_over_cpu": (gpu_value / est_value) if est_value else None},
+        "configs_scored_per_s": n_s / dt_s,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps of the headline workload (default 5 for large)")
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="large", choices=["tiny", "mid", "whole_layer", "large", "batched"],
+                    help="headline workload: its figures are the top-level fields of the line")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads for the `workloads` block (default: whole_layer next to "
+                         "large, large next to whole_layer; 'none' for the headline alone)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
+    ap.add_argument("--serial-score", action="store_true",
+                    help="score on the main stream before the sweep instead of beside it on a second stream")
+    ap.add_argument("--no-early-exit", action="store_true", help="skip the extra timing of the sweep with early exit at the knee")
+    ap.add_argument("--no-per-k", action="store_true", help="skip the extra timing of the Lloyd step for single values of k")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 1 GiB (reference for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_1905_12799_amd import binding as rls
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    rls.lib()   # fails loudly when the HIP library is not built
+
+    head = args.workload
+    if args.also is None:
+        also = {"large": ["whole_layer"], "whole_layer": ["large"]}.get(head, [])
+    else:
+        also = [n for n in args.also.split(",") if n and n != "none" and n != head]
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[head][0]
+    warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[head][1]
+
+    blocks = {}
+    for name in also:      # the other workloads first, with their own (default) step counts
+        s, wu = DEFAULT_STEPS[name]
+        blocks[name] = run_workload(name, s, wu, args)
+    blocks[head] = run_workload(head, steps, warmup, args)
+    h = blocks[head]
+
+    out = {
+        "metric": "config_iter_per_s", "value": h["value"], "unit": "config*iter/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": h["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": h["config"], "roofline": h["roofline"],
+    }
+    if "cpu_baseline" in h:
+        out["cpu_baseline"] = h["cpu_baseline"]
+    for key in ("configs_scored_per_s", "sweep_config_iter_per_s", "stage_ms", "gbt_score", "early_exit", "lloyd_step_per_k"):
+        if key in h:
+            out[key] = h[key]
+    out["library_version"] = rls.version()
+    out["workloads"] = {n: {k: v for k, v in b.items() if n != head or k in ("value", "ms_per_step", "steps", "warmup", "config", "roofline", "cpu_baseline")}
+                        for n, b in blocks.items()}
     print(json.dumps(out))
     return 0
 

@@ -86,7 +86,8 @@ typedef struct {
  * score_dev[i] = base + sum_t leaf_t(walk_t(X[i])), added in fp32 in tree order t = 0, 1, ...
  *   X_dev      [N][ldx] fp32, first d columns used
  *   score_dev  [N] fp32 (written)
- * Feature indices outside [0, d) are a precondition violation (not checked on the device).
+ * A feature index outside [0, d) is read as the nearest valid column (0 or d - 1): the forest lives in device
+ * memory, which the host checks never read, and the walk must not leave the row.
  */
 int32_t rls_gbt_score(const rls_forest *forest, const float *X_dev, int64_t N, int32_t d, int64_t ldx,
                       float *score_dev, void *stream);
@@ -249,16 +250,6 @@ int32_t rls_replace_visited(int32_t *cfg_dev, int32_t k, int32_t n_knobs, const 
  */
 int32_t rls_apply_actions(const int32_t *cfg_dev, const int8_t *action_dev, int64_t m, const rls_knob_domains *domains,
                           int32_t *cfg_out_dev, float *features_dev, int64_t ldf, void *stream);
-
-/*
- * Timing aid for benchmarks (not part of the paper's method).  While enabled, rls_kmeans_sweep[_batched]
- * records a pair of HIP events on `stream` around every launch of the Lloyd step kernel (the fused
- * assign + update pass that dominates Algorithm 1's k-means calls).  rls_profile_read waits for the
- * recorded events, returns how many launches were timed and their summed duration in milliseconds,
- * and forgets them.  Not thread-safe; events are created by the library on first use.
- */
-int32_t rls_profile_enable(int32_t on);
-int32_t rls_profile_read(int32_t *n_launches, double *total_ms);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "rls_internal.h"), os.path.join(ROOT, "include", "rls.h")]
+    deps = sources() + [os.path.join(CSRC, "rls_internal.h"), os.path.join(ROOT, "include", "rls.h"),
+                        os.path.join(ROOT, "include", "rls_bench.h")]
     return any(os.path.getmtime(p) > t for p in deps)
 
 

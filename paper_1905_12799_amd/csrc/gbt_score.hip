@@ -7,6 +7,8 @@
 // values to its own fp32 running sum in tree order, which makes the result independent of the launch shape.
 // A step of the walk is two dependent LDS reads and four vector instructions: the walk keeps the node's LDS
 // address a (node n of a tree at byte b sits at b + 8 n) and moves to child 2n + 1 + c by a <- 2 a + (8 + 8 c - b).
+#include <mutex>
+
 #include "rls_internal.h"
 
 namespace rls {
@@ -14,6 +16,10 @@ namespace rls {
 namespace {
 
 constexpr int kForestChunkBytes = 96 * 1024;   // with the 64 KB tile of configurations this fills the 160 KB of LDS
+// Entries (internal nodes, and leaves) a thread carries in registers for the next chunk: enough for a chunk of
+// kForestChunkBytes of deep trees at 512 threads.  Shallow trees have more leaves per byte (2^D leaves in 12 2^D - 8
+// bytes), so the launcher also caps the trees per chunk by kStage * threads leaves.
+constexpr int kStage = (kForestChunkBytes / 12 + 511) / 512 + 1;
 
 __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int64_t N, int d, int64_t ldx,
                                  float *__restrict__ score, int trees_per_chunk)
@@ -46,9 +52,7 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
     }
 
     // The next chunk of the forest travels in registers while the current one is walked: its loads are issued
-    // before the walk (unconditional, indices clamped) and written to LDS after it.  kStage entries per thread
-    // cover a chunk of kForestChunkBytes at 512 threads.
-    constexpr int kStage = (kForestChunkBytes / 12 + 511) / 512 + 1;
+    // before the walk (unconditional, indices clamped) and written to LDS after it.
     int st_feat[kStage];
     float st_thr[kStage], st_leaf[kStage];
     auto fetch_chunk = [&](int t0, int tc) {
@@ -126,19 +130,23 @@ hipError_t launch_gbt_score(const ForestArgs *forests_host, int32_t batch, const
                             int64_t ldx, int64_t x_batch_stride, float *score, hipStream_t s)
 {
     const int P = d <= 16 ? 1024 : 512;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gbt_score_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::once_flag attr_once;
+    static hipError_t attr_status = hipSuccess;
+    std::call_once(attr_once, [] {
+        attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(gbt_score_kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    if (attr_status != hipSuccess) return attr_status;
     for (int32_t b = 0; b < batch; ++b) {
         const ForestArgs &f = forests_host[b];
         const int64_t tree_bytes = (((int64_t)1 << f.depth) - 1) * 8 + ((int64_t)1 << f.depth) * 4;
         int tpc = (int)(kForestChunkBytes / tree_bytes);
+        // a thread stages kStage entries of the next chunk: its leaves (the larger of the two arrays) must fit
+        const int64_t stage_cap = ((int64_t)kStage * P) >> f.depth;
+        if (tpc > stage_cap) tpc = (int)stage_cap;
         if (tpc < 1) tpc = 1;
         if (tpc > f.n_trees) tpc = f.n_trees;
+        if (((int64_t)tpc << f.depth) > (int64_t)kStage * P) return hipErrorInvalidValue;   // depth <= 12: cannot happen
         const size_t lds = (size_t)d * P * 4 + (size_t)tpc * tree_bytes;
         const unsigned grid = (unsigned)((N + P - 1) / P);
         hipLaunchKernelGGL(gbt_score_kernel, dim3(grid), dim3(P), lds, s, f, X + (int64_t)b * x_batch_stride, N, (int)d,

@@ -19,6 +19,7 @@
 //            equal a fresh sum in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel
 //            adds them to the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
 // The final pass replaces the update by the fp64 loss of every point and the label output.
+#include <mutex>
 #include <type_traits>
 
 #include "rls_internal.h"
@@ -1349,19 +1350,21 @@ __global__ void lloyd_loss_kernel(int n_runs, int n_chunks, const int32_t *statu
 template <int DP>
 hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const SweepArgs &a, hipStream_t s)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the kernels' LDS limit is raised once per process, whichever host thread comes first
+    static std::once_flag attr_once;
+    static hipError_t attr_status = hipSuccess;
+    std::call_once(attr_once, [] {
         const void *fns[] = {
             reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, false>),
             reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, true>),
             reinterpret_cast<const void *>(lloyd_step_kernel<DP, true, false>),
         };
         for (const void *fn : fns) {
-            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) attr_status = e;
         }
-        attr_set = true;
-    }
+    });
+    if (attr_status != hipSuccess) return attr_status;
     const int batch = a.batch;
     // column statistics
     hipLaunchKernelGGL(colstats_kernel, dim3(L.stat_blocks, batch), dim3(kThreads), 0, s, a.X, a.N, (int)a.d, DP, a.ldx,

@@ -143,8 +143,9 @@ __global__ void visited_apply_kernel(int32_t *__restrict__ cfg, int k, int n_kno
 
 // Configuration updater of the search agent (Sec. 4.1 of the paper): one thread per (configuration, knob) adds the
 // direction to the domain index and holds it at the domain's borders; optionally writes the knob's value as feature.
-__global__ void apply_actions_kernel(const int32_t *__restrict__ cfg, const signed char *__restrict__ action, int64_t m,
-                                     DomainArgs dm, int32_t *__restrict__ cfg_out, float *__restrict__ features, int64_t ldf)
+// (cfg and cfg_out may be the same array: neither is declared restrict; a thread reads its element before it writes it)
+__global__ void apply_actions_kernel(const int32_t *cfg, const signed char *__restrict__ action, int64_t m,
+                                     DomainArgs dm, int32_t *cfg_out, float *__restrict__ features, int64_t ldf)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= m * dm.n_knobs) return;

@@ -2,6 +2,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "rls_internal.h"
@@ -12,14 +14,17 @@ static thread_local hipError_t g_last_hip = hipSuccess;
 void set_hip_error(hipError_t e) { g_last_hip = e; }
 
 // ---- benchmark timing: event pairs around the Lloyd step kernel --------------------------------
-static bool g_profile_on = false;
+// (bench-only state, see rls_bench.h; everything below g_profile_mutex is guarded by it)
+static std::atomic<bool> g_profile_on{false};
+static std::mutex g_profile_mutex;
 static std::vector<hipEvent_t> g_events;     // pool, reused
 static size_t g_events_used = 0;             // events recorded since the last read (even: begin, odd: end)
 
-bool profile_enabled() { return g_profile_on; }
+bool profile_enabled() { return g_profile_on.load(std::memory_order_relaxed); }
 
 hipError_t profile_mark(hipStream_t s, bool begin)
 {
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     if (begin != (g_events_used % 2 == 0)) return hipSuccess;   // keep pairs aligned
     if (g_events_used == g_events.size()) {
         hipEvent_t ev;
@@ -81,13 +86,14 @@ int32_t rls_last_hip_error(void) { return (int32_t)g_last_hip; }
 
 int32_t rls_profile_enable(int32_t on)
 {
-    g_profile_on = on != 0;
+    g_profile_on.store(on != 0, std::memory_order_relaxed);
     return RLS_OK;
 }
 
 int32_t rls_profile_read(int32_t *n_launches, double *total_ms)
 {
     if (!n_launches || !total_ms) return RLS_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_profile_mutex);
     double sum = 0.0;
     const size_t pairs = g_events_used / 2;
     for (size_t i = 0; i < pairs; ++i) {

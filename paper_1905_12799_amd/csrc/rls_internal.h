@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "rls.h"
+#include "rls_bench.h"
 
 namespace rls {
 
@@ -79,7 +80,7 @@ struct SweepLayout {
     int64_t chain;          // int64 [k_max] seeding chain
     int64_t mind;           // fp64 [N] squared distance to the nearest chosen centre
     int64_t bsum;           // fp64 [seed blocks] block sums of mind
-    int64_t opA;            // per 32-row tile: bf16 pieces of the centred, -2-scaled centroids and the bias slot, in MFMA operand order
+    int64_t opA;            // per 32-row tile: fp16 pieces of the centred, -2-scaled centroids and the bf16 bias slot, in MFMA operand order
     int64_t cnmax;          // fp32 [n_runs] per-run maximum of cn
     int64_t psum;           // int64 [n_chunks][total_rows][d] per-chunk changes of the fixed-point sums
     int64_t pcnt;           // int32 [n_chunks][total_rows] per-chunk changes of the member counts
@@ -148,7 +149,7 @@ struct SweepArgs {
     int32_t *status;              // [batch]
     char *ws;                     // workspace base
 };
-// benchmark timing of the Lloyd step kernel (see rls_profile_enable)
+// benchmark timing of the Lloyd step kernel (see rls_bench.h)
 bool profile_enabled();
 hipError_t profile_mark(hipStream_t s, bool begin);
 

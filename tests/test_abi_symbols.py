@@ -1,5 +1,6 @@
-"""The C-ABI library loads and exports every symbol include/rls.h declares (no compute calls: no GPU needed)."""
+"""The C-ABI library loads and exports every symbol the headers under include/ declare (no compute calls: no GPU needed)."""
 import ctypes
+import glob
 import os
 import re
 
@@ -9,9 +10,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "rls.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rls_[a-z_]+)\s*\(", text)))
+    names = set()
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert any(h.endswith("rls.h") for h in headers)
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(rls_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 @pytest.fixture(scope="module")

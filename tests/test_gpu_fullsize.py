@@ -1,10 +1,18 @@
 """GPU parity at the full sizes of the workloads, in the launch configuration bench.py times.
 
 The oracle cannot sweep every k at these sizes in test time, so each test runs the full sweep on the GPU and
-compares (a) complete oracle runs for a few k, bit for bit as in test_gpu_parity.py, and (b) for every k,
-sampled points: the label the GPU wrote must be the oracle's argmin against the centroids the GPU returned
-(the final assignment is defined against the returned centroids), plus properties that hold at any size.
+compares (a) the oracle's complete runs stored under tests/golden/ by make_fullsize_golden.py (which calls the oracle
+only): labels and centroids bit for bit through SHA-256 hashes, the loss within 1e-5, the seeding chain, and the k
+that the knee test of Algorithm 1 picks on both loss curves - every k of the 1M workload, the k up to past the knee
+plus a middle and the largest k at 8M, every k of eight of the 64 batched spaces; (b) complete runs by the oracle as
+built on this machine for a few k, bit for bit as in test_gpu_parity.py (more of them when the stored runs were made
+for an input this machine's generator does not reproduce); and (c) for every k, sampled points: the label the GPU
+wrote must be the oracle's argmin against the centroids the GPU returned (the final assignment is defined against
+the returned centroids), plus properties that hold at any size.
 """
+import hashlib
+import json
+import os
 import sys
 import time
 
@@ -35,9 +43,11 @@ def progress(msg):
     sys.__stderr__.flush()
 
 
-def check_run_against_oracle(orc, X, chain, k, iters, labels_g, C_g, J_g):
+def check_run_against_oracle(orc, X, chain, k, iters, labels_g, C_g, J_g, J_out=None):
     progress(f"oracle Lloyd N={X.shape[0]} k={k} rounds={iters}")
     labels_o, C_o, J_o, _ = orc.lloyd(X, k, iters, chain)
+    if J_out is not None:
+        J_out[k] = J_o
     bad = np.flatnonzero(labels_g != labels_o)
     for i in bad[:50]:
         d1, d2, _ = orc.two_nearest(X[i], C_o)
@@ -50,6 +60,58 @@ def check_run_against_oracle(orc, X, chain, k, iters, labels_g, C_g, J_g):
     if len(bad) == 0:
         np.testing.assert_array_equal(C_g, C_o, err_msg=f"k={k}: centroids not bit-identical")
     return len(bad)
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+KNEE_CONSTANTS = (1.01, 1.05, 1.1, 1.5, 2.0)
+
+
+def sha(a):
+    return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+
+
+def stored_oracle_runs(name, b, X):
+    """The oracle's full-size results written by tests/golden/make_fullsize_golden.py for space b of a workload, or
+    None when the file is missing or was made for another input (the generator's output differs on this machine)."""
+    path = os.path.join(GOLDEN, f"fullsize_{name}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        g = json.load(fh)
+    space = g["spaces"].get(str(b))
+    if space is None or space["x_sha256"] != sha(X):
+        return None
+    return space
+
+
+def check_against_stored_oracle(rls, orc, space, res, k_min, k_max, b=None):
+    """Every stored run: labels and centroids bit for bit (by hash), loss within 1e-5 relative; then the knee of
+    Algorithm 1 on both loss curves.  Returns the list of k compared."""
+    lab = res.labels if b is None else res.labels[b]
+    J_g = (res.inertia if b is None else res.inertia[b]).cpu().numpy()
+    ks = sorted(int(k) for k in space["runs"])
+    for k in ks:
+        run = space["runs"][str(k)]
+        J_o = float.fromhex(run["inertia"])
+        assert sha(lab[k - k_min].cpu().numpy()) == run["labels_sha256"], f"k={k}: labels differ from the oracle's"
+        assert sha(res.centroids_of(k, b).cpu().numpy()) == run["centroids_sha256"], f"k={k}: centroids differ"
+        assert abs(J_g[k - k_min] - J_o) <= 1e-5 * max(J_o, 1e-300), f"k={k}: inertia {J_g[k - k_min]} vs {J_o}"
+    # chosen k: the oracle's curve is known on the leading range k_min .. k_top; Algorithm 1 stops at the first k
+    # whose test fires, so a knee below k_top is the knee of the whole curve
+    k_top = k_min
+    while k_top + 1 in ks and k_top in ks:
+        k_top += 1
+    if k_min in ks and k_top > k_min:
+        J_o = [float.fromhex(space["runs"][str(k)]["inertia"]) for k in range(k_min, k_top + 1)]
+        decided = 0
+        for const in KNEE_CONSTANTS:
+            k_o = orc.pick_knee(J_o, k_min, k_top, const)
+            assert rls.pick_knee(J_g[:k_top - k_min + 1].tolist(), k_min, k_top, const) == k_o
+            if k_o < k_top or k_top == k_max:
+                assert rls.pick_knee(J_g.tolist(), k_min, k_max, const) == k_o, f"chosen k, constant {const}"
+                decided += 1
+        assert decided >= 2, "the stored range must reach past the knee for some constants"
+    return ks
 
 
 def check_sampled_points(orc, X, res, k_min, k_max, rng, per_k=64, b=None):
@@ -80,11 +142,29 @@ def test_whole_layer_full(rls, orc):
     chain = orc.kmeanspp_chain(p.X, w.k_max, w.seed)
     np.testing.assert_array_equal(rls.kmeanspp_chain(X, w.k_max, w.seed).cpu().numpy(), chain)
     J = res.inertia.cpu().numpy()
+    space = stored_oracle_runs("whole_layer", 0, p.X)
+    if space is not None:
+        progress("whole_layer: every k against the stored oracle runs")
+        np.testing.assert_array_equal(chain, np.array(space["chain"], dtype=np.int64))
+        assert check_against_stored_oracle(rls, orc, space, res, w.k_min, w.k_max) == list(range(w.k_min, w.k_max + 1))
+        live = (7,)                                # one run by the oracle as it is built here, as a cross-check of the file
+    else:
+        progress("whole_layer: no stored oracle runs for this input: oracle runs for the k up to the knee and three more")
+        live = tuple(range(1, 13)) + (24, 33, 64)
     exempt = 0
-    for k in (1, 7, 24, 33, 64):
+    J_o = {}
+    for k in live:
         exempt += check_run_against_oracle(orc, p.X, chain, k, w.iters, res.labels[k - w.k_min].cpu().numpy(),
-                                           res.centroids_of(k).cpu().numpy(), J[k - w.k_min])
+                                           res.centroids_of(k).cpu().numpy(), J[k - w.k_min], J_out=J_o)
     assert exempt == 0
+    if space is None:
+        decided = 0
+        for const in KNEE_CONSTANTS:
+            k_o = orc.pick_knee([J_o[k] for k in range(1, 13)], 1, 12, const)
+            if k_o < 12:        # the test fired inside the range the oracle ran: that is the knee of the whole curve
+                assert rls.pick_knee(J.tolist(), w.k_min, w.k_max, const) == k_o
+                decided += 1
+        assert decided >= 2
     check_sampled_points(orc, p.X, res, w.k_min, w.k_max, np.random.default_rng(1))
     # tree scores of the same trajectory, sampled rows against the oracle
     scores = rls.gbt_score(rls.DeviceForest.from_host(p.forest), X).cpu().numpy()
@@ -141,6 +221,16 @@ def test_large_full(rls, orc):
     assert np.all(t[:, 1:] <= t[:, :-1] * (1 + 1e-6))
     np.testing.assert_array_equal(t[:, -1], res.inertia.cpu().numpy())
     check_sampled_points(orc, p.X, res, w.k_min, w.k_max, np.random.default_rng(3), per_k=24)
+    space = stored_oracle_runs("large", 0, p.X)
+    if space is not None:
+        progress("large: all rounds against the stored oracle runs (k up to past the knee, a middle and the largest k)")
+        np.testing.assert_array_equal(chain, np.array(space["chain"], dtype=np.int64))
+        ks = check_against_stored_oracle(rls, orc, space, res, w.k_min, w.k_max)
+        assert len(ks) >= 12
+    else:
+        progress("large: no stored oracle runs for this input: one complete oracle run of all rounds")
+        check_run_against_oracle(orc, p.X, chain, 3, w.iters, res.labels[3 - w.k_min].cpu().numpy(),
+                                 res.centroids_of(3).cpu().numpy(), float(res.inertia[3 - w.k_min]))
     # k = 1: the centroid is the exact column mean
     mean = (p.X.astype(np.float64).sum(axis=0) / w.N).astype(np.float32)
     np.testing.assert_allclose(res.centroids_of(1).cpu().numpy()[0], mean, rtol=1e-6, atol=1e-6)
@@ -163,12 +253,28 @@ def test_batched_full(rls, orc):
     res = rls.kmeans_sweep_batched(X, w.k_min, w.k_max, w.iters, seeds=seeds)
     torch.cuda.synchronize()
     J = res.inertia.cpu().numpy()
-    for b in (0, 41, 63):
+    n_stored = 0
+    for b in range(w.batch):
+        space = stored_oracle_runs("batched", b, probs[b].X)
+        if space is not None:
+            progress(f"batched: space {b}, every k against the stored oracle runs")
+            check_against_stored_oracle(rls, orc, space, res, w.k_min, w.k_max, b=b)
+            n_stored += 1
+    for b in ((41,) if n_stored else (0, 41, 63)):
         p = probs[b]
         chain = orc.kmeanspp_chain(p.X, w.k_max, seeds[b])
-        for k in (5, 32):
+        J_o = {}
+        for k in ((5, 32) if n_stored else tuple(range(1, 13)) + (32,)):
             check_run_against_oracle(orc, p.X, chain, k, w.iters, res.labels[b, k - w.k_min].cpu().numpy(),
-                                     res.centroids_of(k, b).cpu().numpy(), J[b, k - w.k_min])
+                                     res.centroids_of(k, b).cpu().numpy(), J[b, k - w.k_min], J_out=J_o)
+        if not n_stored:
+            decided = 0
+            for const in KNEE_CONSTANTS:
+                k_o = orc.pick_knee([J_o[k] for k in range(1, 13)], 1, 12, const)
+                if k_o < 12:
+                    assert rls.pick_knee(J[b].tolist(), w.k_min, w.k_max, const) == k_o
+                    decided += 1
+            assert decided >= 2
     for b in (7, 30):
         check_sampled_points(orc, probs[b].X, res, w.k_min, w.k_max, np.random.default_rng(b), per_k=16, b=b)
     forests = [rls.DeviceForest.from_host(p.forest) for p in probs]
