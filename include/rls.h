@@ -145,6 +145,23 @@ int32_t rls_kmeans_sweep(const float *X_dev, int64_t N, int32_t d, int64_t ldx,
                          void *workspace_dev, int64_t workspace_bytes, void *stream);
 
 /*
+ * rls_kmeans_sweep for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, results and status bits, but the workspace is a fixed
+ * array of RLS_STATIC_WORKSPACE_BYTES inside the library's device image (each GPU the library runs on holds its
+ * own copy until the process ends).  The call allocates nothing and frees nothing.
+ *   - RLS_ERR_WORKSPACE when rls_kmeans_sweep_workspace_bytes(N, d, k_min, k_max, 1) exceeds
+ *     RLS_STATIC_WORKSPACE_BYTES (nothing is enqueued); that query tells beforehand whether a shape fits.
+ *   - All calls on one GPU share that GPU's array: two such sweeps that overlap in time on one GPU (different
+ *     streams or host threads) race.  Successive calls on one stream are fine; every call initialises the parts
+ *     of the array it reads.
+ */
+#define RLS_STATIC_WORKSPACE_BYTES (64 << 20)
+int32_t rls_kmeans_sweep_static(const float *X_dev, int64_t N, int32_t d, int64_t ldx,
+                                int32_t k_min, int32_t k_max, int32_t iters, uint64_t seed,
+                                const int64_t *init_idx_dev, int32_t *labels_dev, float *centroids_dev,
+                                double *inertia_dev, double *inertia_trace_dev, int32_t *status_dev, void *stream);
+
+/*
  * `batch` independent spaces of equal shape in one launch sequence.  Space b reads
  * X_dev + b * x_batch_stride, uses seeds[b] (host array) or init_idx_dev + b * k_max, and writes
  * block b of every output: labels [batch][n_k][N], centroids [batch][sum(k)*d], inertia [batch][n_k],

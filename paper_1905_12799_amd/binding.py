@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.rls_kmeans_sweep.restype = i32
         L.rls_kmeans_sweep.argtypes = [vp, i64, i32, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, vp, vp, i64, vp]
         L.rls_kmeans_sweep_batched.restype = i32
+        L.rls_kmeans_sweep_static.restype = i32
+        L.rls_kmeans_sweep_static.argtypes = [vp, i64, i32, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, vp, vp]
         L.rls_kmeans_sweep_batched.argtypes = [i32, vp, i64, i32, i64, i64, i32, i32, i32, ctypes.POINTER(u64), vp, vp,
                                                vp, vp, vp, vp, vp, i64, vp]
         L.rls_kmeans_sweep_until_knee_workspace_bytes.restype = ctypes.c_int64
@@ -257,6 +259,36 @@ def kmeans_sweep(X: torch.Tensor, k_min: int, k_max: int, iters: int, seed: int 
         if st != 0:
             raise RuntimeError(f"rls_kmeans_sweep: data precondition violated, status bits {st}")
     return SweepResult(k_min, k_max, d, labels, centroids, inertia, trace, status)
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def kmeans_sweep_static(X: torch.Tensor, k_min: int, k_max: int, iters: int, seed: int = 0,
+                        init_idx: Optional[torch.Tensor] = None, want_trace: bool = False,
+                        out: Optional[SweepResult] = None) -> SweepResult:
+    """rls_kmeans_sweep_static: the sweep on the library's own fixed workspace (the call allocates nothing).
+    `out` supplies the output tensors (labels may be None); without it they are allocated here, before the call."""
+    _mat(X, "X")
+    N, d = X.shape
+    n_k = k_max - k_min + 1
+    rows = sum(range(k_min, k_max + 1))
+    dev = X.device
+    if out is None:
+        out = SweepResult(k_min, k_max, d, torch.empty((n_k, N), dtype=torch.int32, device=dev),
+                          torch.empty(rows * d, dtype=torch.float32, device=dev),
+                          torch.empty(n_k, dtype=torch.float64, device=dev),
+                          torch.empty((n_k, iters + 1), dtype=torch.float64, device=dev) if want_trace else None,
+                          torch.empty(1, dtype=torch.int32, device=dev))
+    if init_idx is not None:
+        _dev(init_idx, torch.int64, "init_idx")
+        if init_idx.numel() < k_max:
+            raise ValueError("init_idx needs k_max entries")
+    rc = lib().rls_kmeans_sweep_static(_ptr(X), N, d, X.stride(0), k_min, k_max, iters, ctypes.c_uint64(seed),
+                                       _ptr(init_idx), _ptr(out.labels), _ptr(out.centroids), _ptr(out.inertia),
+                                       _ptr(out.trace), _ptr(out.status), _stream())
+    _check(rc, "rls_kmeans_sweep_static")
+    return out
 
 
 def kmeans_sweep_until_knee(X: torch.Tensor, k_min: int, k_max: int, k_wave: int, iters: int, knee_const: float,

@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librls.so")
-SOURCES = ["rls_api.hip", "gbt_score.hip", "kmeans_seed.hip", "kmeans_lloyd.hip", "snap.hip", "modes_visited.hip"]
+SOURCES = ["rls_api.hip", "gbt_score.hip", "kmeans_seed.hip", "kmeans_lloyd.hip", "snap.hip", "modes_visited.hip",
+           "sweep_static.hip"]
 
 
 def sources():
