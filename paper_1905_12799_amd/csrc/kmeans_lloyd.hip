@@ -289,8 +289,18 @@ __device__ inline void insert2(int key, int &m1, int &m2)
     m1 = min(m1, key);
 }
 
+// insert two keys at once: the new smallest is the smallest of {m1, a, b} (one min3); the second smallest of
+// {m1, m2, a, b} is the smaller of m2 and the second smallest of {m1, a, b} (one med3, one min), because m2 >= m1
+__device__ inline void insert2x2(int a, int b, int &m1, int &m2)
+{
+    const int second = med3i(m1, a, b);
+    m1 = min(m1, min(a, b));
+    m2 = min(m2, second);
+}
+
 // fold the 16 results of one 32x32 tile (4 quads of 4 rows) into the per-run states: the two smallest keys
-// (three vector instructions per distance: and-or, med3, min).  The second one shows whether the first is a clear winner.
+// (five vector instructions per two distances: two and-or, min3, med3, min).  The second key shows whether the
+// first is a clear winner.
 template <int S, int ST>
 __device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int mask, int (&m1)[ST], int (&m2)[ST])
 {
@@ -298,7 +308,9 @@ __device__ inline void fold_tile(const floatx16 &acc, const int (&kidx)[16], int
     for (int q = 0; q < 4; ++q) {
         const int st = state_of<S>(q);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) insert2(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), m1[st], m2[st]);
+        for (int i = 0; i < 4; i += 2)
+            insert2x2(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), pack_key(acc[4 * q + i + 1], mask, kidx[4 * q + i + 1]),
+                      m1[st], m2[st]);
     }
 }
 
@@ -348,7 +360,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     constexpr int ST = S == 1 ? 4 : (S == 2 ? 2 : 1);   // runs owned by a lane
     constexpr int SLAB_ = 32 * NB;                  // points a wave takes at a time
     constexpr int NM = 3 * NK + 1;                  // MFMAs per tile block
-    constexpr int VPER = (48 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
+    constexpr int VPER = (40 + 16 + NM - 1) / NM;   // vector ops to slot in after each MFMA of a chain
     constexpr bool LOSS = FINAL || TRACE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hl = lane >> 5;
