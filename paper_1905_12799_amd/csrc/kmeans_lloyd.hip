@@ -4,7 +4,10 @@
 // Per iteration one launch of lloyd_step_kernel covers every (group of runs, chunk of points).  A workgroup
 // stages its group's operand rows, a copy of its centroids and integer accumulators in LDS once; then each of
 // its waves (twelve up to d_pad = 16, eight at 32) works through its own points without any barrier:
-//   load     each lane loads its half of the features of its points straight into registers, one step ahead
+//   load     each lane loads its half of the features of its points straight into registers, one step ahead; from
+//            the second round on the lanes load the matrix operands themselves, which lloyd_prepare_kernel derives
+//            once per sweep from the rows (centred, scaled, split into fp16 pieces, squared norm), and a raw row
+//            is read again only for a point that needs it: a close call or a changed label
 //   assign   distances in the expansion |c'|^2 + |x'|^2 - 2 x'.c' on data centred by the column means and scaled
 //            by one power of two into fp16 range, on the 16-bit matrix pipeline: every fp32 operand is split
 //            into two fp16 pieces (22 significant bits) and the three leading cross products are accumulated
@@ -58,6 +61,16 @@ __host__ __device__ constexpr int ksteps_of(int dp) { return dp == 32 ? 2 : 1; }
 __host__ __device__ constexpr int tile_slots_of(int dp) { return 2 * ksteps_of(dp) + 1; }          // 16-byte slots per lane
 __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(dp) * 64 * 16; }    // per 32-row tile
 
+// Prepared copy of the points (written once per sweep by lloyd_prepare_kernel): per block of 32 points the B operands
+// of the distance tiles in the lane order of the step kernel - 2 * ksteps slots (high pieces, then low pieces, per
+// K-step) of 64 lanes x 16 bytes - followed by 32 entries of 16 bytes with the point's squared norm (its three bf16
+// pieces as the bias slot wants them, then the fp32 value).
+// Moved pairs of the rounds that run on the prepared copy: every wave keeps a ring of records in global memory
+// (point within the chunk, run, new label | old label) and works it off 64 records at a time.
+constexpr int kLogCap = 512;                  // records per wave (a slab adds at most 4 x 64; 63 may be left over)
+__host__ __device__ constexpr int prep_slots_of(int dp) { return 2 * ksteps_of(dp); }
+__host__ __device__ constexpr int prep_block_u4_of(int dp) { return prep_slots_of(dp) * 64 + 32; }   // 16-byte units per block
+
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
 struct Carve {
     int opA, cs, sums, cnts, misc, total;
@@ -90,7 +103,7 @@ struct StepArgs {
     const int32_t *status;   // [batch]
     char *ws;                // workspace base
     int64_t ws_bs;           // bytes per batch element
-    int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev;
+    int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev, off_xp, off_log;
     int32_t first_round;     // 1: no point has a label yet (every pair enters a cluster, nothing leaves one)
 };
 
@@ -100,6 +113,18 @@ __device__ inline long long to_fixed(float x, int shift)
 {
     const double t = trunc(ldexp((double)x, shift));
     return __double_as_longlong(__dadd_rn(t, 6755399441055744.0)) - 0x4338000000000000ll;
+}
+
+// The accumulators hold "biased" fixed-point rows: the bit pattern of the double 2^52 + 2^51 + x * 2^shift, which is
+// kFixBias plus the two's complement integer x * 2^shift.  A row that enters a cluster adds its patterns, a row that
+// leaves subtracts them, so an accumulator is off by kFixBias times the net number of rows - the member count delta,
+// which is tracked anyway - and the bias is taken out once per chunk.  For a column whose values are all multiples of
+// 2^-shift the product is an exact integer and one fused multiply-add (by the power of two 2^shift, whose high word
+// comes from LDS) yields the pattern: two vector instructions per feature.
+constexpr unsigned long long kFixBias = 0x4338000000000000ull;
+__device__ inline unsigned long long fixed_biased(float x, int pow2_hi)
+{
+    return (unsigned long long)__double_as_longlong(fma((double)x, __hiloint2double(pow2_hi, 0), 6755399441055744.0));
 }
 
 // The part of x below the column grid 2^-shift, scaled by 2^(shift + kLowBits): the bits that to_fixed drops.
@@ -294,7 +319,9 @@ __device__ inline void insert2(int key, int &m1, int &m2)
 __device__ inline void insert2x2(int a, int b, int &m1, int &m2)
 {
     const int second = med3i(m1, a, b);
-    m1 = min(m1, min(a, b));
+    // (written as one instruction: left to itself the compiler takes two minima here; the operands are packed keys,
+    // results of vector instructions, so no wait states of the matrix pipeline are involved)
+    asm("v_min3_i32 %0, %1, %2, %3" : "=v"(m1) : "v"(m1), "v"(a), "v"(b));
     m2 = min(m2, second);
 }
 
@@ -327,9 +354,12 @@ struct WaveCtx {
     const float *mu_s;            // LDS: -(column mean * scale) [32]
     float scale;                  // power of two that brings the centred data into fp16 range
     const int *shift_s;           // LDS: fixed-point shifts [32]
+    const int *pow2hi_s;          // LDS: high words of the doubles 2^shift [32]
     const int *wide_s;            // LDS: wide-column flags [32], any at [32]
     const float *cnmax_s;         // LDS: per-run maximum squared norm of the centred centroids [8]
     const float *X;               // this space's rows
+    const uint4 *xp;              // global: prepared copy of this space's points (see prep_block_u4_of)
+    unsigned long long *log;      // global: this wave's ring of moved-pair records [kLogCap]
     int64_t ldx, N;
     int d, k0, n_runs, n_tiles, grow0;
     unsigned char *prev;          // global: labels of the last round for the group's runs, [run][N]
@@ -345,9 +375,12 @@ struct WaveCtx {
 // VEC: rows of X may be read 16 bytes at a time.  A template parameter and not a run-time branch: with both load
 // paths in one function the compiler merges them into 4-byte loads, and a wave's rows then cost four times the
 // cache look-ups (which bounds sweeps over few k).
-template <int DP, int S, bool FINAL, bool TRACE, bool VEC>
+// PRE: the operands come from the prepared copy; the raw rows are read on demand (not in a pass that sums the loss,
+// which needs every row, and not in the first round, where every row enters a cluster).
+template <int DP, int S, bool FINAL, bool TRACE, bool VEC, bool PRE>
 __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 {
+    static_assert(!PRE || (!FINAL && !TRACE), "the prepared copy serves the plain assign + update pass only");
     constexpr int NB = slab_blocks_of(DP, S);       // blocks of 32 points per wave and slab
     // with 2 blocks at d_pad = 32 the rows of the next slab are requested after the tile loop, when the operand
     // registers are free again, instead of before it
@@ -381,11 +414,19 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     // values are used) and nothing touches their registers before settle(), so no wait is placed early.
     // Addresses are a wave-uniform base (the slab's first row) plus a 32-bit lane offset: the row index inside
     // the slab is clamped to the chunk's last row, the feature offset to the row's last 16 bytes.
-    float xnext[NB][HP];
+    float xnext[PRE ? 1 : NB][PRE ? 1 : HP];
+    constexpr int NP = prep_slots_of(DP);            // operand slots per lane and block in the prepared copy
+    uint4 pnext[PRE ? NB : 1][PRE ? NP : 1];          // PRE: the operand slots of the slab being fetched
+    uint4 nnext[PRE ? NB : 1];                        // PRE: its norm entries
     const unsigned ldx32 = (unsigned)c.ldx;          // checked on the host: 64 rows of ldx floats fit 32 bits
-    unsigned foff[H];                                // this lane's clamped feature offsets (fixed for the launch)
+    // this lane's clamped feature offsets (fixed for the launch; with the prepared copy they are worked out where
+    // a row is read, which is rare, instead of being kept in registers)
+    auto feat_off = [&](int s) { return (unsigned)(VEC ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1)); };
+    unsigned foff[PRE ? 1 : H];
+    if constexpr (!PRE) {
 #pragma unroll
-    for (int s = 0; s < H; ++s) foff[s] = (unsigned)(VEC ? min(f0 + (s & ~3), d - 4) + (s & 3) : min(f0 + s, d - 1));
+        for (int s = 0; s < H; ++s) foff[s] = feat_off(s);
+    }
     int oldn[NB][ST];                                // previous labels of the slab being fetched
     unsigned run_off[ST];                            // offset of this lane's runs in the label arrays (runs are N apart)
 #pragma unroll
@@ -397,6 +438,21 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     auto fetch = [&](int64_t slab_base) {
         const float *Xs = c.X + slab_base * c.ldx;
         const unsigned last = (unsigned)min((int64_t)(SLAB_ - 1), c.chunk_end - 1 - slab_base);
+        if constexpr (PRE) {
+            const int64_t blk0 = slab_base >> 5, blk_last = (c.chunk_end - 1) >> 5;     // chunks start on a block boundary
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb) {
+                const uint4 *bp = c.xp + min(blk0 + pb, blk_last) * prep_block_u4_of(DP);
+#pragma unroll
+                for (int sl = 0; sl < NP; ++sl) pnext[pb][sl] = bp[sl * 64 + lane];
+                nnext[pb] = bp[NP * 64 + n];
+                const unsigned li = min((unsigned)(pb * 32 + n), last);
+                const unsigned char *prev_slab = c.prev + slab_base;
+#pragma unroll
+                for (int st = 0; st < ST; ++st) oldn[pb][st] = (int)prev_slab[run_off[st] + li];
+            }
+            return;
+        }
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             const unsigned li = min((unsigned)(pb * 32 + n), last);
@@ -421,10 +477,20 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     };
     // the outstanding loads of fetch() have to be complete here
     auto settle = [&]() {
+        if constexpr (PRE) {
 #pragma unroll
-        for (int pb = 0; pb < NB; ++pb)
+            for (int pb = 0; pb < NB; ++pb) {
 #pragma unroll
-            for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xnext[pb][s]));
+                for (int sl = 0; sl < NP; ++sl)
+                    asm volatile("" : "+v"(pnext[pb][sl].x), "+v"(pnext[pb][sl].y), "+v"(pnext[pb][sl].z), "+v"(pnext[pb][sl].w));
+                asm volatile("" : "+v"(nnext[pb].x), "+v"(nnext[pb].y), "+v"(nnext[pb].z));
+            }
+        } else {
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xnext[pb][s]));
+        }
         if (!FINAL) {
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb)
@@ -456,6 +522,62 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     double jown[ST];                                 // loss sums of the runs this lane owns
 #pragma unroll
     for (int st = 0; st < ST; ++st) jown[st] = 0.0;
+    // ---- the log of moved pairs (PRE): records [log_head, log_tail) of the ring are waiting
+    int log_head = 0, log_tail = 0;                  // wave-uniform
+    auto log_flush = [&](int nrec) {
+        // Works off `nrec` <= 64 records: DP lanes per record, one feature each - the row is read (a coalesced read of
+        // one row per record), put on the fixed-point grid and moved from the old cluster's accumulators to the new
+        // one's.  Integer adds: the order in which records are worked off does not matter.
+        constexpr int LPR = DP, RPS = 64 / LPR, STEPS = 64 / RPS, BATCH = STEPS < 8 ? STEPS : 8;   // rows in flight (16 costs more registers than it saves in waiting)
+        // The records were written by other lanes of this wave: their stores must have been issued to the memory
+        // system before the reads.  Both go through this compute unit's own first-level cache, so workgroup scope is
+        // enough (a wider scope would write back the second-level cache, which costs more than the whole flush).
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        unsigned long long rec = 0ull;
+        if (lane < nrec) rec = __hip_atomic_load(&c.log[(unsigned)(log_head + lane) & (kLogCap - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int l = lane % LPR, g = lane / LPR;
+        for (int s0 = 0; s0 < STEPS && s0 * RPS < nrec; s0 += BATCH) {
+            unsigned lo[BATCH], hi[BATCH];
+            float xv[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int src = (s0 + u) * RPS + g;
+                lo[u] = (unsigned)__shfl((int)(unsigned)rec, src, 64);
+                hi[u] = (unsigned)__shfl((int)(unsigned)(rec >> 32), src, 64);
+                const bool ok = src < nrec && l < d;
+                xv[u] = ok ? c.X[(c.chunk_begin + (int64_t)(lo[u] & 0x1ffffu)) * c.ldx + l] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int src = (s0 + u) * RPS + g;
+                if (src < nrec && l < d) {
+                    const int r = (int)((lo[u] >> 20) & 7u), nl = (int)((lo[u] >> 24) & 127u), ol = (int)(hi[u] & 0xffu);
+                    const int rowbase = r * c.k0 + r * (r - 1) / 2;
+                    const unsigned long long v = any_wide ? (unsigned long long)to_fixed(xv[u], c.shift_s[l]) + kFixBias
+                                                          : fixed_biased(xv[u], c.pow2hi_s[l]);
+                    const int cp = src & (c.copies - 1);
+                    unsigned long long *sc = c.sums + (int64_t)cp * c.real_rows * (DP + 1);
+                    atomicAdd(sc + (rowbase + nl) * (DP + 1) + l, v);
+                    if (l == 0) atomicAdd(&c.cnts[cp * c.real_rows + rowbase + nl], 1);
+                    if (ol != 0xff) {
+                        __hip_atomic_fetch_sub(sc + (rowbase + ol) * (DP + 1) + l, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (l == 0) atomicAdd(&c.cnts[cp * c.real_rows + rowbase + ol], -1);
+                    }
+                    if (any_wide && c.wide_s[l] != 0) {
+                        // bits below the grid of a wide column go to a global integer accumulator (rare)
+                        const long long low = fixed_low(xv[u], c.shift_s[l]);
+                        if (low != 0) {
+                            const int64_t crow = c.grow0 + rowbase;
+                            if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + l]), (unsigned long long)(-low));
+                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + l]), (unsigned long long)low);
+                        }
+                    }
+                }
+            }
+        }
+        log_head += nrec;
+    };
     int cur = wave;
     if (cur >= n_slabs) return;
     fetch(c.chunk_begin + (int64_t)cur * SLAB);
@@ -465,13 +587,16 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     while (cur < n_slabs) {
         const int64_t base = c.chunk_begin + (int64_t)cur * SLAB;     // first point of this wave's slab
         // (a lane past the end of the chunk holds a copy of the chunk's last row: its pairs are never active)
+        // (PRE: the raw rows are not there yet; the lanes that need theirs load them after the fold)
         float xraw[NB][HP];
+        if constexpr (!PRE) {
 #pragma unroll
-        for (int pb = 0; pb < NB; ++pb) {
+            for (int pb = 0; pb < NB; ++pb) {
 #pragma unroll
-            for (int s = 0; s < HP; ++s) xraw[pb][s] = s < H ? xnext[pb][s] : 0.0f;
+                for (int s = 0; s < HP; ++s) xraw[pb][s] = s < H ? xnext[pb][s] : 0.0f;
+            }
         }
-        if (d < DP) {
+        if (!PRE && d < DP) {
             // padded features: the clamped loads brought real values of other features, they count as zero
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb)
@@ -488,6 +613,23 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         float xn[NB];
         int m1[NB][ST], m2[NB][ST];
         int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
+        if constexpr (PRE) {
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb) {
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) {
+                    bx[pb][0][ks] = as_f16x8(pnext[pb][0 * NK + ks]);
+                    bx[pb][1][ks] = as_f16x8(pnext[pb][1 * NK + ks]);
+                }
+                xn[pb] = __uint_as_float(nnext[pb].z);
+                bb[pb] = hl ? as_bf16x8(make_uint4(nnext[pb].x, nnext[pb].y, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
+#pragma unroll
+                for (int st = 0; st < ST; ++st) {
+                    m1[pb][st] = kBigKey; m2[pb][st] = kBigKey;
+                    oldl[pb][st] = oldn[pb][st];
+                }
+            }
+        } else {
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             float xc[HP];
@@ -514,6 +656,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 m1[pb][st] = kBigKey; m2[pb][st] = kBigKey;
                 oldl[pb][st] = oldn[pb][st];        // fetched with the rows, a slab ago
             }
+        }
         }
 
         // The rows and previous labels of the next slab are asked for now and only needed when that slab starts, a
@@ -612,6 +755,49 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
         }
 
+        if constexpr (PRE) {
+            // Raw rows on demand: the exact arithmetic of a close call needs the point's row; both lanes of such a
+            // point (each holds half of the features) load their half.  (The exact sums need the rows of the points
+            // whose label changed: those are read when the wave works off its log of moved pairs.)
+            unsigned need = pend;
+            need |= xchg32(need);
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int s = 0; s < HP; ++s) {
+                    if (s < H) asm volatile("" : "=v"(xraw[pb][s]));     // defined, whatever it holds: read only where loaded
+                    else xraw[pb][s] = 0.0f;
+                }
+            if (__ballot(need != 0u) != 0ull) {
+                const float *Xs = c.X + base * c.ldx;
+                // (the row index is made opaque here so that the offsets below are worked out on the spot: hoisted out
+                // of the slab loop they would sit in registers, or in spill slots, through the tile loop)
+                unsigned nrow = (unsigned)n;
+                asm volatile("" : "+v"(nrow));
+#pragma unroll
+                for (int pb = 0; pb < NB; ++pb) {
+                    if ((need >> (pb * ST)) & ((1u << ST) - 1u)) {       // an active pair: the point lies inside the chunk
+                        const unsigned ro = ((unsigned)(pb * 32) + nrow) * ldx32;
+                        if (VEC) {
+#pragma unroll
+                            for (int c4 = 0; c4 < H / 4; ++c4) {
+                                const float4 v = *reinterpret_cast<const float4 *>(Xs + (ro + feat_off(4 * c4)));
+                                xraw[pb][4 * c4 + 0] = v.x; xraw[pb][4 * c4 + 1] = v.y; xraw[pb][4 * c4 + 2] = v.z; xraw[pb][4 * c4 + 3] = v.w;
+                            }
+                        } else {
+#pragma unroll
+                            for (int s = 0; s < H; ++s) xraw[pb][s] = Xs[ro + feat_off(s)];
+                        }
+                        if (d < DP) {
+#pragma unroll
+                            for (int s = 0; s < H; ++s)
+                                if (s >= nf) xraw[pb][s] = 0.0f;
+                        }
+                    }
+                }
+            }
+        }
+
         // A close call (about one pair in a thousand on knob data; every pair where centroids coincide or integer
         // data ties exactly) is settled by the whole wave with the exact arithmetic over the run.  The point's row is
         // read out of the registers of the two lanes that hold its halves.
@@ -660,7 +846,28 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             }
         }
 
-        if (!FINAL) {
+        if constexpr (PRE) {
+            // Exact sums, later: the moved pairs go into this wave's log; 64 records at a time are worked off below.
+#pragma unroll
+            for (int i = 0; i < NBST; ++i) {
+                const bool has = (mv >> i) & 1u;
+                const unsigned long long bal = __ballot(has);
+                if (bal != 0ull) {
+                    const int pb = i / ST, st = i % ST;
+                    const unsigned rl = S == 8 ? 0u : (unsigned)(hl * ST + st);
+                    const unsigned pos = (unsigned)log_tail +
+                                         __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+                    if (has) {
+                        const unsigned pt = (unsigned)(base - c.chunk_begin) + (unsigned)(pb * 32 + n);    // below 2^17
+                        const unsigned lo = pt | (rl << 20) | ((unsigned)(m1[pb][st] & 127) << 24);
+                        c.log[pos & (kLogCap - 1)] = ((unsigned long long)(unsigned)oldl[pb][st] << 32) | lo;
+                    }
+                    log_tail += (int)__popcll(bal);
+                }
+            }
+            while (log_tail - log_head >= 64) log_flush(64);
+        }
+        if (!FINAL && !PRE) {
             // Exact sums: a point whose label changed moves its fixed-point row from the old cluster to the new
             // one.  Both lanes of the point's pair take part (each holds half of the features); one pair per pass.
             const unsigned mvo = xchg32(mv);
@@ -678,11 +885,19 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             };
             if (__ballot(both != 0u) != 0ull) {
                 // this lane's half of its points' rows on the fixed-point grid (zero beyond the last feature)
-                long long fx[NB][H];
+                unsigned long long fx[NB][H];
+                if (any_wide) {
+                    // some column has bits below its grid: those are cut off here (and summed apart, see add_low)
 #pragma unroll
-                for (int pb = 0; pb < NB; ++pb)
+                    for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
-                    for (int s = 0; s < H; ++s) fx[pb][s] = to_fixed(xraw[pb][s], c.shift_s[f0 + s]);   // xraw is 0 past the last feature
+                        for (int s = 0; s < H; ++s) fx[pb][s] = (unsigned long long)to_fixed(xraw[pb][s], c.shift_s[f0 + s]) + kFixBias;
+                } else {
+#pragma unroll
+                    for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                        for (int s = 0; s < H; ++s) fx[pb][s] = fixed_biased(xraw[pb][s], c.pow2hi_s[f0 + s]);   // xraw is 0 past the last feature
+                }
                 if (c.first_round) {
                     // no point has a label yet: every pair of the slab enters its cluster, run by run
 #pragma unroll
@@ -701,7 +916,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                             if (pvalid) {
                                 unsigned long long *sn = sums_l + (rowbase + nl) * (DP + 1) + f0;
 #pragma unroll
-                                for (int s = 0; s < H; ++s) atomicAdd(sn + s, (unsigned long long)fx[pb][s]);
+                                for (int s = 0; s < H; ++s) atomicAdd(sn + s, fx[pb][s]);
                                 if (hl == 0) atomicAdd(&cnts_l[rowbase + nl], 1);
                                 if (any_wide) add_low(p, rowbase, 0xff, nl);
                             }
@@ -723,21 +938,21 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     const int rowbase = r * c.k0 + r * (r - 1) / 2;
                     if (act) {
                         unsigned long long *sn = sums_l + (rowbase + nl) * (DP + 1) + f0;
-                        long long v[H];
+                        unsigned long long v[H];
 #pragma unroll
                         for (int s = 0; s < H; ++s) {
                             v[s] = fx[0][s];
 #pragma unroll
                             for (int q = 1; q < NB; ++q)
                                 if (pb == q) v[s] = fx[q][s];
-                            atomicAdd(sn + s, (unsigned long long)v[s]);
+                            atomicAdd(sn + s, v[s]);
                         }
                         if (hl == 0) atomicAdd(&cnts_l[rowbase + nl], 1);
                         if (ol != 0xff) {   // 0xff: no label yet, nothing to take back
                             unsigned long long *so = sums_l + (rowbase + ol) * (DP + 1) + f0;
 #pragma unroll
                             for (int s = 0; s < H; ++s)
-                                __hip_atomic_fetch_sub(so + s, (unsigned long long)v[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                                __hip_atomic_fetch_sub(so + s, v[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                             if (hl == 0) atomicAdd(&cnts_l[rowbase + ol], -1);
                         }
                         if (any_wide) add_low(base + pb * 32 + n, rowbase, ol, nl);
@@ -804,6 +1019,9 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         cur = nxt;
         nxt = nxt2;
     }
+    if constexpr (PRE) {
+        if (log_tail > log_head) log_flush(log_tail - log_head);
+    }
     if (LOSS) {
         // hand the sums over by run: run r of the group is owned by half-wave r / ST (by the lower one when S = 8)
 #pragma unroll
@@ -814,18 +1032,18 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     }
 }
 
-template <int DP, bool FINAL, bool TRACE, bool VEC>
+template <int DP, bool FINAL, bool TRACE, bool VEC, bool PRE>
 __device__ inline void wave_loop_of(int S, const WaveCtx &c, double (&jloc)[8])
 {
     switch (S) {
-    case 1: wave_loop<DP, 1, FINAL, TRACE, VEC>(c, jloc); break;
-    case 2: wave_loop<DP, 2, FINAL, TRACE, VEC>(c, jloc); break;
-    case 4: wave_loop<DP, 4, FINAL, TRACE, VEC>(c, jloc); break;
-    default: wave_loop<DP, 8, FINAL, TRACE, VEC>(c, jloc); break;
+    case 1: wave_loop<DP, 1, FINAL, TRACE, VEC, PRE>(c, jloc); break;
+    case 2: wave_loop<DP, 2, FINAL, TRACE, VEC, PRE>(c, jloc); break;
+    case 4: wave_loop<DP, 4, FINAL, TRACE, VEC, PRE>(c, jloc); break;
+    default: wave_loop<DP, 8, FINAL, TRACE, VEC, PRE>(c, jloc); break;
     }
 }
 
-template <int DP, bool FINAL, bool TRACE>
+template <int DP, bool FINAL, bool TRACE, bool PRE>
 __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPlan plan, StepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -853,6 +1071,7 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     int *wide_s = reinterpret_cast<int *>(smem + cv.misc + 256);          // [32] + any at [32]
     float *cnmax_s = reinterpret_cast<float *>(smem + cv.misc + 400);     // [8]
     int *next_slab = reinterpret_cast<int *>(smem + cv.misc + 448);
+    int *pow2hi_s = reinterpret_cast<int *>(smem + cv.misc + 1536);       // [32]
     double *jpart = reinterpret_cast<double *>(smem + cv.misc + 512);     // [8][WV]
 
     const int tid = threadIdx.x;
@@ -865,7 +1084,11 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
         const float *colmean = reinterpret_cast<const float *>(wsb + a.off_colinfo);
         const int *colshift = reinterpret_cast<const int *>(wsb + a.off_colinfo + 128);
         const int *colwide = reinterpret_cast<const int *>(wsb + a.off_colinfo + 256);
-        if (tid < 32) { mu_s[tid] = tid < DP ? colmean[tid] : 0.0f; shift_s[tid] = colshift[tid]; }   // colmean: already negated and scaled
+        if (tid < 32) {
+            mu_s[tid] = tid < DP ? colmean[tid] : 0.0f;                    // colmean: already negated and scaled
+            shift_s[tid] = colshift[tid];
+            pow2hi_s[tid] = (1023 + colshift[tid]) << 20;                 // 2^shift as a double: the high word
+        }
         if (tid < 33) wide_s[tid] = colwide[tid];
         const uint4 *src = reinterpret_cast<const uint4 *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
         for (int e = tid; e < g.n_tiles * (tile_bytes_of(DP) / 16); e += TH) opA_s[e] = src[e];
@@ -889,8 +1112,10 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     c.opA_s = opA_s;
     c.cs = cs_lds;            // the group's centroids as given, rows padded to d + 4 floats
     c.next_slab = next_slab;
-    c.sums = sums; c.cnts = cnts; c.copies = copies; c.real_rows = real_rows; c.mu_s = mu_s; c.shift_s = shift_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
+    c.sums = sums; c.cnts = cnts; c.copies = copies; c.real_rows = real_rows; c.mu_s = mu_s; c.shift_s = shift_s; c.pow2hi_s = pow2hi_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
     c.scale = *reinterpret_cast<const float *>(wsb + a.off_colinfo + kColScaleOff);
+    c.xp = reinterpret_cast<const uint4 *>(wsb + a.off_xp);
+    c.log = reinterpret_cast<unsigned long long *>(wsb + a.off_log) + ((int64_t)blockIdx.x * WV + (tid >> 6)) * kLogCap;
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
     c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
     c.labels_out = (FINAL && a.labels) ? a.labels + (int64_t)b * a.lab_bs + (int64_t)g.run0 * a.N : nullptr;
@@ -916,8 +1141,8 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     for (int i = 0; i < 8; ++i) jloc[i] = 0.0;
 
     if (c.chunk_begin < c.chunk_end) {
-        if (c.vec_x) wave_loop_of<DP, FINAL, TRACE, true>(g.S, c, jloc);
-        else wave_loop_of<DP, FINAL, TRACE, false>(g.S, c, jloc);
+        if (c.vec_x) wave_loop_of<DP, FINAL, TRACE, true, PRE>(g.S, c, jloc);
+        else wave_loop_of<DP, FINAL, TRACE, false, PRE>(g.S, c, jloc);
     }
 
     if (FINAL || TRACE) {
@@ -937,8 +1162,12 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
                                    ((int64_t)chunk * plan.total_rows + grow0) * d;
         for (int e = tid; e < real_rows * d; e += TH) {
             unsigned long long v = 0ull;
-            for (int cp = 0; cp < copies; ++cp) v += sums[(cp * real_rows + e / d) * (DP + 1) + e % d];
-            psum[e] = v;
+            long long rows_in = 0;     // rows that entered minus rows that left: each carried the bias once
+            for (int cp = 0; cp < copies; ++cp) {
+                v += sums[(cp * real_rows + e / d) * (DP + 1) + e % d];
+                rows_in += cnts[cp * real_rows + e / d];
+            }
+            psum[e] = v - kFixBias * (unsigned long long)rows_in;
         }
         int *pcnt = reinterpret_cast<int *>(wsb + a.off_pcnt) + (int64_t)chunk * plan.total_rows + grow0;
         for (int e = tid; e < real_rows; e += TH) {
@@ -1074,6 +1303,57 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
     if (wide) atomicOr(&flags, 1 << 16);
     __syncthreads();
     if (l == 0) { colwide[32] = (flags >> 16) & 1; status[b] = flags & 0xffff; }
+}
+
+// ---- the prepared copy of the points (see prep_block_u4_of): what the step kernel would derive from a row in every
+//      launch and for every group of runs - centring, scaling, the two fp16 pieces, the squared norm - done once per sweep.
+//      One thread per (point, half of the features), in the lane order of the step kernel; the arithmetic is the
+//      step kernel's own, instruction for instruction.
+template <int DP>
+__global__ void __launch_bounds__(256) lloyd_prepare_kernel(const float *__restrict__ X, int64_t N, int d, int64_t ldx, int64_t x_bs,
+                                                            const int32_t *__restrict__ status, char *ws, int64_t ws_bs,
+                                                            int64_t off_colinfo, int64_t off_xp)
+{
+    constexpr int H = DP / 2, NK = ksteps_of(DP), HP = 8 * NK;
+    const int b = blockIdx.y;
+    if (status[b] != 0) return;
+    char *wsb = ws + (int64_t)b * ws_bs;
+    const float *Xb = X + (int64_t)b * x_bs;
+    const float *colmean = reinterpret_cast<const float *>(wsb + off_colinfo);      // -(mean * scale)
+    const float scale = *reinterpret_cast<const float *>(wsb + off_colinfo + kColScaleOff);
+    uint4 *xp = reinterpret_cast<uint4 *>(wsb + off_xp);
+    const int64_t n_blocks = (N + 31) / 32;
+    const int lane = threadIdx.x & 63, n = lane & 31, hl = lane >> 5;
+    const int f0 = hl * H;
+    for (int64_t blk = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); blk < n_blocks;
+         blk += (int64_t)gridDim.x * (blockDim.x >> 6)) {
+        const int64_t p = blk * 32 + n;
+        float xc[HP];
+        float part = 0.0f;
+#pragma unroll
+        for (int s = 0; s < HP; ++s) {
+            const int f = f0 + s;
+            const float x = (s < H && f < d && p < N) ? Xb[p * ldx + f] : 0.0f;
+            // a point past the end and a padded feature count as a zero of the centred data
+            xc[s] = (s < H && f < d && p < N) ? fmaf(x, scale, colmean[f]) : 0.0f;
+            part = fmaf(xc[s], xc[s], part);
+        }
+        const float xn = part + xchg32(part);
+        uint4 *bp = xp + blk * prep_block_u4_of(DP);
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            unsigned ph[4], pl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) split2_pair(xc[8 * ks + 2 * i], xc[8 * ks + 2 * i + 1], ph[i], pl[i]);
+            bp[(0 * NK + ks) * 64 + lane] = make_uint4(ph[0], ph[1], ph[2], ph[3]);
+            bp[(1 * NK + ks) * 64 + lane] = make_uint4(pl[0], pl[1], pl[2], pl[3]);
+        }
+        if (hl == 0) {
+            unsigned nh, nm, nl;
+            split3(xn, nh, nm, nl);
+            bp[prep_slots_of(DP) * 64 + n] = make_uint4(nh | (nm << 16), nl, __float_as_uint(xn), 0u);
+        }
+    }
 }
 
 // ---- start of a sweep: padding operand rows are zero vectors with a huge norm; running totals are zero;
@@ -1367,9 +1647,10 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     static hipError_t attr_status = hipSuccess;
     std::call_once(attr_once, [] {
         const void *fns[] = {
-            reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, false>),
-            reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, true>),
-            reinterpret_cast<const void *>(lloyd_step_kernel<DP, true, false>),
+            reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, false, false>),
+            reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, false, true>),
+            reinterpret_cast<const void *>(lloyd_step_kernel<DP, false, true, false>),
+            reinterpret_cast<const void *>(lloyd_step_kernel<DP, true, false, false>),
         };
         for (const void *fn : fns) {
             const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -1383,6 +1664,15 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
                        a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
     hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(32), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
                        L.per_batch, L.colstat_part, L.colinfo, a.status);
+    {
+        // the prepared copy: one wave per block of 32 points, a few blocks per wave
+        const int64_t n_blocks = (a.N + 31) / 32;
+        int64_t grid_x = (n_blocks + 4 * 8 - 1) / (4 * 8);      // 4 waves per workgroup, ~8 blocks per wave
+        if (grid_x > 4096) grid_x = 4096;
+        if (grid_x < 1) grid_x = 1;
+        hipLaunchKernelGGL((lloyd_prepare_kernel<DP>), dim3((unsigned)grid_x, batch), dim3(256), 0, s, a.X, a.N, (int)a.d, a.ldx,
+                           a.x_batch_stride, a.status, a.ws, L.per_batch, L.colinfo, L.xp);
+    }
     InitArgs ia;
     ia.ws = a.ws; ia.ws_bs = L.per_batch;
     ia.off_opA = L.opA; ia.off_losum = L.losum; ia.off_tot = L.tot; ia.off_totcnt = L.totcnt; ia.off_prev = L.prev;
@@ -1407,6 +1697,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     sa.status = a.status; sa.ws = a.ws; sa.ws_bs = L.per_batch;
     sa.off_colinfo = L.colinfo; sa.off_opA = L.opA; sa.off_cnmax = L.cnmax;
     sa.off_psum = L.psum; sa.off_pcnt = L.pcnt; sa.off_pj = L.pj; sa.off_losum = L.losum; sa.off_prev = L.prev;
+    sa.off_xp = L.xp; sa.off_log = L.log;
 
     size_t lds = 0;
     for (int gi = 0; gi < plan.n_groups; ++gi) {
@@ -1422,17 +1713,20 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         sa.first_round = t == 0 ? 1 : 0;
         if (prof) { hipError_t e = profile_mark(s, true); if (e != hipSuccess) return e; }
         if (trace) {
-            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
+            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, true, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
             hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws,
                                L.per_batch, L.pj, a.trace, (int64_t)plan.n_runs * (a.iters + 1), (int64_t)(a.iters + 1), (int64_t)t);
         } else {
-            hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
+            // the first round brings every row into a cluster and reads the rows themselves; later rounds take the
+            // operands from the prepared copy and read a row only where a label is in doubt or has changed
+            if (t == 0) hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
+            else hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, true>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
         }
         hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
     }
-    hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
+    hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
     hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws, L.per_batch,
                        L.pj, a.inertia, (int64_t)plan.n_runs, (int64_t)1, (int64_t)0);
     if (trace)
@@ -1563,6 +1857,8 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->tot = take((int64_t)plan.total_rows * d * 16);
     L->totcnt = take((int64_t)plan.total_rows * d * 8);
     L->prev = take(align_up((int64_t)plan.n_runs * N, 16));
+    L->xp = take((N + 31) / 32 * prep_block_u4_of(plan.dp) * 16);
+    L->log = take((int64_t)plan.n_groups * plan.n_chunks * (step_threads_of(plan.dp) / 64) * kLogCap * 8);
     L->per_batch = off;
     L->total = off * batch;
 }

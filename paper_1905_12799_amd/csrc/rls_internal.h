@@ -89,6 +89,8 @@ struct SweepLayout {
     int64_t tot;            // int64 [total_rows][d][2] running 128-bit fixed-point sums (hi, lo)
     int64_t totcnt;         // int64 [total_rows][d] running member counts (one copy per feature)
     int64_t prev;           // uint8 [n_runs][N] label of every point in the last round (0xff: none yet)
+    int64_t log;            // uint64 [groups * chunks][waves][512] rings of moved-pair records, one per wave of the step kernel
+    int64_t xp;             // prepared copy of the points: per block of 32, the matrix operands and squared norms (kmeans_lloyd.hip)
     int64_t per_batch;      // bytes per batch element (multiple of 256)
     int64_t total;          // per_batch * batch
     int32_t seed_blocks;

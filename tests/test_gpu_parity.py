@@ -292,6 +292,17 @@ def run_both(rls, orc, X, k_min, k_max, iters, seed=None, init=None, trace=True)
         res = rls.kmeans_sweep(Xd, k_min, k_max, iters, seed=seed, want_trace=trace)
         ref = orc.kmeans_sweep(X, k_min, k_max, iters, seed=seed, want_trace=trace)
     torch.cuda.synchronize()
+    if trace:
+        # Without the loss trace the rounds after the first run a different kernel path (operands from a copy of the
+        # points prepared once per sweep, rows read on demand): it must give the same sweep, bit for bit.
+        if init is not None:
+            plain = rls.kmeans_sweep(Xd, k_min, k_max, iters, init_idx=dev(init))
+        else:
+            plain = rls.kmeans_sweep(Xd, k_min, k_max, iters, seed=seed)
+        torch.cuda.synchronize()
+        assert torch.equal(plain.labels, res.labels), "labels differ between the sweep with and without trace"
+        assert torch.equal(plain.centroids, res.centroids), "centroids differ between the sweep with and without trace"
+        assert torch.equal(plain.inertia, res.inertia)
     return res, ref
 
 
