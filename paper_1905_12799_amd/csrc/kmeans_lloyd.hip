@@ -63,13 +63,13 @@ __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(d
 
 // Prepared copy of the points (written once per sweep by lloyd_prepare_kernel): per block of 32 points the B operands
 // of the distance tiles in the lane order of the step kernel - 2 * ksteps slots (high pieces, then low pieces, per
-// K-step) of 64 lanes x 16 bytes - followed by 32 entries of 16 bytes with the point's squared norm (its three bf16
-// pieces as the bias slot wants them, then the fp32 value).
+// K-step) of 64 lanes x 16 bytes - followed by 32 entries of 8 bytes with the point's squared norm as the three bf16
+// pieces the bias slot wants (their sum, which is the norm cut off below 2^-24 of itself, serves the error bound).
+__host__ __device__ constexpr int prep_slots_of(int dp) { return 2 * ksteps_of(dp); }
+__host__ __device__ constexpr int prep_block_u4_of(int dp) { return prep_slots_of(dp) * 64 + 16; }   // 16-byte units per block
 // Moved pairs of the rounds that run on the prepared copy: every wave keeps a ring of records in global memory
 // (point within the chunk, run, new label | old label) and works it off 64 records at a time.
 constexpr int kLogCap = 512;                  // records per wave (a slab adds at most 4 x 64; 63 may be left over)
-__host__ __device__ constexpr int prep_slots_of(int dp) { return 2 * ksteps_of(dp); }
-__host__ __device__ constexpr int prep_block_u4_of(int dp) { return prep_slots_of(dp) * 64 + 32; }   // 16-byte units per block
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
 struct Carve {
@@ -417,7 +417,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     float xnext[PRE ? 1 : NB][PRE ? 1 : HP];
     constexpr int NP = prep_slots_of(DP);            // operand slots per lane and block in the prepared copy
     uint4 pnext[PRE ? NB : 1][PRE ? NP : 1];          // PRE: the operand slots of the slab being fetched
-    uint4 nnext[PRE ? NB : 1];                        // PRE: its norm entries
+    uint2 nnext[PRE ? NB : 1];                        // PRE: its norm entries
     const unsigned ldx32 = (unsigned)c.ldx;          // checked on the host: 64 rows of ldx floats fit 32 bits
     // this lane's clamped feature offsets (fixed for the launch; with the prepared copy they are worked out where
     // a row is read, which is rare, instead of being kept in registers)
@@ -445,7 +445,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 const uint4 *bp = c.xp + min(blk0 + pb, blk_last) * prep_block_u4_of(DP);
 #pragma unroll
                 for (int sl = 0; sl < NP; ++sl) pnext[pb][sl] = bp[sl * 64 + lane];
-                nnext[pb] = bp[NP * 64 + n];
+                nnext[pb] = reinterpret_cast<const uint2 *>(bp + NP * 64)[n];
                 const unsigned li = min((unsigned)(pb * 32 + n), last);
                 const unsigned char *prev_slab = c.prev + slab_base;
 #pragma unroll
@@ -483,7 +483,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int sl = 0; sl < NP; ++sl)
                     asm volatile("" : "+v"(pnext[pb][sl].x), "+v"(pnext[pb][sl].y), "+v"(pnext[pb][sl].z), "+v"(pnext[pb][sl].w));
-                asm volatile("" : "+v"(nnext[pb].x), "+v"(nnext[pb].y), "+v"(nnext[pb].z));
+                asm volatile("" : "+v"(nnext[pb].x), "+v"(nnext[pb].y));
             }
         } else {
 #pragma unroll
@@ -621,7 +621,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     bx[pb][0][ks] = as_f16x8(pnext[pb][0 * NK + ks]);
                     bx[pb][1][ks] = as_f16x8(pnext[pb][1 * NK + ks]);
                 }
-                xn[pb] = __uint_as_float(nnext[pb].z);
+                xn[pb] = (__uint_as_float(nnext[pb].x << 16) + __uint_as_float(nnext[pb].x & 0xffff0000u)) + __uint_as_float(nnext[pb].y << 16);
                 bb[pb] = hl ? as_bf16x8(make_uint4(nnext[pb].x, nnext[pb].y, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
 #pragma unroll
                 for (int st = 0; st < ST; ++st) {
@@ -1351,7 +1351,7 @@ __global__ void __launch_bounds__(256) lloyd_prepare_kernel(const float *__restr
         if (hl == 0) {
             unsigned nh, nm, nl;
             split3(xn, nh, nm, nl);
-            bp[prep_slots_of(DP) * 64 + n] = make_uint4(nh | (nm << 16), nl, __float_as_uint(xn), 0u);
+            reinterpret_cast<uint2 *>(bp + prep_slots_of(DP) * 64)[n] = make_uint2(nh | (nm << 16), nl);
         }
     }
 }
