@@ -16,7 +16,7 @@ its own step counts stated inside).  Each block carries
                 library on the launch stream during the timed steps.  Its contraction runs on the fp16 matrix
                 pipeline, so `frac` is the method's distance arithmetic (2 d k flop per point and (k, round)) over
                 the launch time over the dense fp16 MFMA peak; beside it the fraction of HBM peak the same launch
-                would need if every k read the trajectory on its own (`hbm_equivalent_frac`, can exceed 1: one read
+                would need if every k read the trajectory on its own (`hbm_equivalent_ratio`, can exceed 1: one read
                 serves up to eight k), the matrix work actually issued, and - from rocprofv3 counters of this
                 library version, else null - the HBM bytes really moved and the vector-issue utilisation
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload, with the scaling to the sweep's mix of k
@@ -42,8 +42,11 @@ VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4.0   # wave64 vector instructions per secon
 # plain 1 GiB copy gives for each counter; lloyd_step_<workload>_sq_counters.md: SQ_INSTS_VALU).  Valid only for the
 # library version they were taken with; any other version reports null.
 COUNTERS = {
-    "whole_layer": {"version": 110, "fetch_kib": 169259.2, "write_kib": 59620.2, "fetch_scale": 2.0, "write_scale": 1.0,
-                    "valu_insts": 2.17e8},
+    # mean over the 30 rounds of a sweep (first round included, like the launches the events time)
+    "whole_layer": {"version": 120, "fetch_kib": 223870.0, "write_kib": 72440.0, "fetch_scale": 2.0, "write_scale": 1.0,
+                    "valu_insts": 1.679e8},
+    "large": {"version": 120, "fetch_kib": 22397000.0, "write_kib": 966300.0, "fetch_scale": 2.0, "write_scale": 1.0,
+              "valu_insts": 5.299e9},
 }
 DEFAULT_STEPS = {"tiny": (50, 5), "mid": (20, 5), "whole_layer": (10, 3), "large": (5, 2), "batched": (5, 2)}
 
@@ -192,11 +195,12 @@ def run_workload(name, steps, warmup, args):
         "kernel": "lloyd_step_kernel", "launches_timed": n_launch, "avg_launch_ms": kernel_s * 1e3,
         "algorithmic_flops_per_launch": alg_flops, "algorithmic_bytes_per_launch": alg_bytes,
         "mfma_issued_frac": issued_flops / kernel_s / 1e12 / MFMA_F16_PEAK_TFLOPS,
-        "fp32_mfma_equivalent_frac": tflops / MFMA_F32_PEAK_TFLOPS,
+        "fp32_mfma_equivalent_ratio": tflops / MFMA_F32_PEAK_TFLOPS,   # against the fp32 matrix peak an fp32 contraction would have had
         "hbm_equivalent_GBps": alg_bytes / kernel_s / 1e9,
-        "hbm_equivalent_frac": alg_bytes / kernel_s / 1e9 / HBM_PEAK_GBS,
+        "hbm_equivalent_ratio": alg_bytes / kernel_s / 1e9 / HBM_PEAK_GBS,   # can pass 1: one read of a row serves up to eight k
         "hbm_traffic_frac": None, "valu_issue_frac": None,
-        "limiting_resource": "vector instruction issue (see valu_issue_frac when counters of this library version exist)",
+        "limiting_resource": "vector instruction issue beside the matrix pipeline, at the clock the chip holds under this load "
+                             "(valu_issue_frac is counted at the nominal 2.4 GHz; profiles/lloyd_step_*_sq_counters.md)",
     }
     hc = COUNTERS.get(w.name)
     if hc is not None and hc["version"] == rls.version() and want_labels:

@@ -1664,7 +1664,12 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
                        a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
     hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(32), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
                        L.per_batch, L.colstat_part, L.colinfo, a.status);
-    {
+    // Rounds after the first run on the prepared copy of the points - unless the loss of every round is wanted (that
+    // pass needs every row), or the sweep is so light in distance work (a single k up to 32: one tile of centroids per
+    // group) that reading the rows is what it costs: the prepared copy is 6 to 12% larger than the rows.
+    const bool trace = a.trace != nullptr;
+    const bool use_pre = !trace && a.iters >= 2 && plan.total_tiles >= 2 * plan.n_groups;
+    if (use_pre) {
         // the prepared copy: one wave per block of 32 points, a few blocks per wave
         const int64_t n_blocks = (a.N + 31) / 32;
         int64_t grid_x = (n_blocks + 4 * 8 - 1) / (4 * 8);      // 4 waves per workgroup, ~8 blocks per wave
@@ -1707,7 +1712,6 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         if (need > lds) lds = need;
     }
     const dim3 grid(plan.n_groups * plan.n_chunks, batch);
-    const bool trace = a.trace != nullptr;
     const bool prof = profile_enabled();
     for (int t = 0; t < a.iters; ++t) {
         sa.first_round = t == 0 ? 1 : 0;
@@ -1720,7 +1724,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         } else {
             // the first round brings every row into a cluster and reads the rows themselves; later rounds take the
             // operands from the prepared copy and read a row only where a label is in doubt or has changed
-            if (t == 0) hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
+            if (t == 0 || !use_pre) hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             else hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, true>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
         }
