@@ -68,7 +68,7 @@ __host__ __device__ constexpr int tile_bytes_of(int dp) { return tile_slots_of(d
 __host__ __device__ constexpr int prep_slots_of(int dp) { return 2 * ksteps_of(dp); }
 __host__ __device__ constexpr int prep_block_u4_of(int dp) { return prep_slots_of(dp) * 64 + 16; }   // 16-byte units per block
 // Moved pairs of the rounds that run on the prepared copy: every wave keeps a ring of records in global memory
-// (point within the chunk, run, new label | old label) and works it off 64 records at a time.
+// (point within the chunk, accumulator row of the new label | row of the old label) and works it off 64 records at a time.
 constexpr int kLogCap = 512;                  // records per wave (a slab adds at most 4 x 64; 63 may be left over)
 
 // ---- LDS carve of lloyd_step_kernel (bytes), shared by the planner and the kernel ------------
@@ -537,6 +537,11 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         if (lane < nrec) rec = __hip_atomic_load(&c.log[(unsigned)(log_head + lane) & (kLogCap - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         const int l = lane % LPR, g = lane / LPR;
+        // this lane's feature column in its copy of the accumulators (the lane group picks the copy)
+        const int cp = g & (c.copies - 1);
+        unsigned long long *const scol = c.sums + (int64_t)cp * c.real_rows * (DP + 1) + l;
+        int *const ccol = c.cnts + cp * c.real_rows;
+        const float *const xcol = c.X + c.chunk_begin * c.ldx + l;
         for (int s0 = 0; s0 < STEPS && s0 * RPS < nrec; s0 += BATCH) {
             unsigned lo[BATCH], hi[BATCH];
             float xv[BATCH];
@@ -546,31 +551,27 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 lo[u] = (unsigned)__shfl((int)(unsigned)rec, src, 64);
                 hi[u] = (unsigned)__shfl((int)(unsigned)(rec >> 32), src, 64);
                 const bool ok = src < nrec && l < d;
-                xv[u] = ok ? c.X[(c.chunk_begin + (int64_t)(lo[u] & 0x1ffffu)) * c.ldx + l] : 0.0f;
+                xv[u] = ok ? xcol[(int64_t)(lo[u] & 0x1ffffu) * c.ldx] : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
                 const int src = (s0 + u) * RPS + g;
                 if (src < nrec && l < d) {
-                    const int r = (int)((lo[u] >> 20) & 7u), nl = (int)((lo[u] >> 24) & 127u), ol = (int)(hi[u] & 0xffu);
-                    const int rowbase = r * c.k0 + r * (r - 1) / 2;
+                    const int nrow = (int)((lo[u] >> 17) & 0xfffu), orow = (int)(hi[u] & 0xffffu);
                     const unsigned long long v = any_wide ? (unsigned long long)to_fixed(xv[u], c.shift_s[l]) + kFixBias
                                                           : fixed_biased(xv[u], c.pow2hi_s[l]);
-                    const int cp = src & (c.copies - 1);
-                    unsigned long long *sc = c.sums + (int64_t)cp * c.real_rows * (DP + 1);
-                    atomicAdd(sc + (rowbase + nl) * (DP + 1) + l, v);
-                    if (l == 0) atomicAdd(&c.cnts[cp * c.real_rows + rowbase + nl], 1);
-                    if (ol != 0xff) {
-                        __hip_atomic_fetch_sub(sc + (rowbase + ol) * (DP + 1) + l, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                        if (l == 0) atomicAdd(&c.cnts[cp * c.real_rows + rowbase + ol], -1);
+                    atomicAdd(scol + nrow * (DP + 1), v);
+                    if (l == 0) atomicAdd(ccol + nrow, 1);
+                    if (orow != 0xffff) {
+                        __hip_atomic_fetch_sub(scol + orow * (DP + 1), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (l == 0) atomicAdd(ccol + orow, -1);
                     }
                     if (any_wide && c.wide_s[l] != 0) {
                         // bits below the grid of a wide column go to a global integer accumulator (rare)
                         const long long low = fixed_low(xv[u], c.shift_s[l]);
                         if (low != 0) {
-                            const int64_t crow = c.grow0 + rowbase;
-                            if (ol != 0xff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + ol) * d + l]), (unsigned long long)(-low));
-                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(crow + nl) * d + l]), (unsigned long long)low);
+                            if (orow != 0xffff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + orow) * d + l]), (unsigned long long)(-low));
+                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + nrow) * d + l]), (unsigned long long)low);
                         }
                     }
                 }
@@ -858,9 +859,13 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     const unsigned pos = (unsigned)log_tail +
                                          __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
                     if (has) {
+                        // the record names the point and the two accumulator rows (within the group) outright, so
+                        // that working it off takes no arithmetic on runs and labels
                         const unsigned pt = (unsigned)(base - c.chunk_begin) + (unsigned)(pb * 32 + n);    // below 2^17
-                        const unsigned lo = pt | (rl << 20) | ((unsigned)(m1[pb][st] & 127) << 24);
-                        c.log[pos & (kLogCap - 1)] = ((unsigned long long)(unsigned)oldl[pb][st] << 32) | lo;
+                        const unsigned rowbase = rl * (unsigned)c.k0 + rl * (rl - 1u) / 2u;
+                        const unsigned lo = pt | ((rowbase + (unsigned)(m1[pb][st] & 127)) << 17);         // rows: below 2^12
+                        const unsigned hi = oldl[pb][st] == 0xff ? 0xffffu : rowbase + (unsigned)oldl[pb][st];
+                        c.log[pos & (kLogCap - 1)] = ((unsigned long long)hi << 32) | lo;
                     }
                     log_tail += (int)__popcll(bal);
                 }
