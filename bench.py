@@ -10,8 +10,8 @@ N x (number of k) x (Lloyd rounds) per step divided by the step time.
 
 Prints ONE JSON line.  The top-level fields describe the headline workload (default: `large`, the 8M x 32
 configuration, the largest one a single GPU is asked to run), timed for exactly --steps steps after --warmup;
-`workloads` holds the same block for every workload of the run (default: the 1M x 16 `whole_layer` as well, with
-its own step counts stated inside).  Each block carries
+`workloads` holds the same block for every workload of the run (default: the 1M x 16 `whole_layer` and the 64 batched
+spaces of 262,144 x 16 as well, with their own step counts stated inside).  Each block carries
   roofline      the dominant kernel (the fused assign + update Lloyd step), timed with HIP events recorded by the
                 library on the launch stream during the timed steps.  Its contraction runs on the fp16 matrix
                 pipeline, so `frac` is the method's distance arithmetic (2 d k flop per point and (k, round)) over
@@ -331,8 +331,8 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["tiny", "mid", "whole_layer", "large", "batched"],
                     help="headline workload: its figures are the top-level fields of the line")
     ap.add_argument("--also", default=None,
-                    help="comma-separated further workloads for the `workloads` block (default: whole_layer next to "
-                         "large, large next to whole_layer; 'none' for the headline alone)")
+                    help="comma-separated further workloads for the `workloads` block (default: whole_layer and batched "
+                         "next to large, large next to whole_layer; 'none' for the headline alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
     ap.add_argument("--serial-score", action="store_true",
@@ -358,7 +358,7 @@ def main() -> int:
 
     head = args.workload
     if args.also is None:
-        also = {"large": ["whole_layer"], "whole_layer": ["large"]}.get(head, [])
+        also = {"large": ["whole_layer", "batched"], "whole_layer": ["large"]}.get(head, [])
     else:
         also = [n for n in args.also.split(",") if n and n != "none" and n != head]
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[head][0]

@@ -849,6 +849,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 
         if constexpr (PRE) {
             // Exact sums, later: the moved pairs go into this wave's log; 64 records at a time are worked off below.
+            static_assert(64 * NBST + 63 <= kLogCap, "a slab's records and what an earlier flush left over must fit the ring");
 #pragma unroll
             for (int i = 0; i < NBST; ++i) {
                 const bool has = (mv >> i) & 1u;
