@@ -212,15 +212,67 @@ __device__ inline int wave_min_i32(int v)
     return v;
 }
 
+__device__ inline float wave_min_f32(float v)
+{
+    v = fminf(v, __int_as_float(dpp_move<kDppSwap1>(__float_as_int(v))));
+    v = fminf(v, __int_as_float(dpp_move<kDppSwap2>(__float_as_int(v))));
+    v = fminf(v, __int_as_float(dpp_move<kDppHalfMirror>(__float_as_int(v))));
+    v = fminf(v, __int_as_float(dpp_move<kDppMirror>(__float_as_int(v))));
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = fminf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    return v;
+}
+
 // The assignment as it is defined, by one whole wave: fp64 direct-form distances sum_l (x_l - c_l)^2, features in
 // rising order, of one point to the k centroids of a run (one or two per lane), then the lexicographic minimum of
 // (distance, index) over the wave.  Every lane returns the winner.  The point arrives as wave-uniform values (read
 // out of the registers of the two lanes that hold its halves); the centroid rows come from the LDS copy, which is
 // zero beyond the last feature, as is the register copy of the point: padded terms add +0.
+//
+// Almost every call is settled by a first stage in fp32: the same direct form (difference, square, sum; all terms
+// are non-negative, so nothing cancels) is within (DP + 2) 2^-24 of the real-number distance, relatively, and the
+// fp64 form within (DP + 2) 2^-53.  A centroid whose fp32 distance exceeds the smallest one by more than 8 (DP + 2)
+// 2^-24 of it (more than twice the two errors and the rounding of the threshold itself) cannot have the smallest
+// fp64 distance; when a single centroid is left it is the winner.  Several left (true ties, duplicated centroids),
+// or a smallest distance so small or large that fp32 may have lost it (below 1e-30, infinite): fp64 over the whole run.
 template <int DP>
 __device__ inline int exact_argmin_wave(const float (&x)[DP], const float *crun, int cstride, int k)
 {
     const int lane = threadIdx.x & 63;
+    {
+        float d32[2] = {INFINITY, INFINITY};        // this lane's centroids: lane and lane + 64 (k <= 128)
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int j = lane + 64 * u;
+            if (u == 1 && k <= 64) break;           // wave-uniform
+            const float *crow = crun + min(j, k - 1) * cstride;
+            float acc = 0.0f;
+#pragma unroll
+            for (int l = 0; l < DP; l += 4) {
+                const float4 cv = *reinterpret_cast<const float4 *>(crow + l);
+                float diff = x[l] - cv.x;
+                acc = fmaf(diff, diff, acc);
+                diff = x[l + 1] - cv.y;
+                acc = fmaf(diff, diff, acc);
+                diff = x[l + 2] - cv.z;
+                acc = fmaf(diff, diff, acc);
+                diff = x[l + 3] - cv.w;
+                acc = fmaf(diff, diff, acc);
+            }
+            if (j < k) d32[u] = acc;
+        }
+        const float wmin = wave_min_f32(fminf(d32[0], d32[1]));
+        const float thr = fmaf(wmin, (float)(8 * (DP + 2)) * 5.9604644775390625e-08f, wmin);
+        const unsigned long long c0 = __ballot(d32[0] <= thr), c1 = __ballot(d32[1] <= thr);
+        if (__popcll(c0) + __popcll(c1) == 1 && wmin >= 1.0e-30f && wmin < INFINITY)
+            return c0 ? __ffsll((long long)c0) - 1 : 63 + __ffsll((long long)c1);
+    }
     double best = INFINITY;
     int arg = 0x7fffffff;
     for (int j = lane; j < k; j += 64) {
@@ -362,7 +414,7 @@ struct WaveCtx {
     unsigned long long *log;      // global: this wave's ring of moved-pair records [kLogCap]
     int64_t ldx, N;
     int d, k0, n_runs, n_tiles, grow0;
-    unsigned char *prev;          // global: labels of the last round for the group's runs, [run][N]
+    unsigned char *prev;          // global: labels of the last round for the group's run slots, [point][8 / S]
     int32_t *labels_out;          // global: labels of the group's runs [run][N] (final pass) or null
     long long *losum;             // global: low-order sums of wide columns [row][d]
     int64_t chunk_begin, chunk_end;
@@ -427,14 +479,24 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
         for (int s = 0; s < H; ++s) foff[s] = feat_off(s);
     }
-    int oldn[NB][ST];                                // previous labels of the slab being fetched
-    unsigned run_off[ST];                            // offset of this lane's runs in the label arrays (runs are N apart)
+    // The labels of the last round are kept per group as one byte per (point, run slot of the group), the R = 8 / S
+    // slots of a point side by side: a lane reads and writes the labels of its ST runs as one word.
+    constexpr int R = 8 / S;                         // run slots of the group
+    using LabWord = std::conditional_t<ST == 4, unsigned, std::conditional_t<ST == 2, unsigned short, unsigned char>>;
+    const unsigned lab_off = S == 8 ? 0u : (unsigned)(hl * ST);     // this lane's first byte within a point's R bytes
+    unsigned oldn[NB];                               // previous labels of the slab being fetched (byte st: run st of this lane)
+    unsigned run_off[ST];                            // offset of this lane's runs in the label output (runs are N apart)
+    unsigned actmask = 0u;                           // bytes of a label word that belong to real runs of this lane
 #pragma unroll
     for (int st = 0; st < ST; ++st) {
         const unsigned rl = S == 8 ? 0u : (unsigned)(hl * ST + st);
         run_off[st] = min(rl, (unsigned)(c.n_runs - 1)) * (unsigned)c.N;
-        for (int pb = 0; pb < NB; ++pb) oldn[pb][st] = 0xff;
+        if (((S == 8) ? (hl == 0) : true) && (int)rl < c.n_runs) actmask |= 0xffu << (8 * st);
     }
+    for (int pb = 0; pb < NB; ++pb) oldn[pb] = 0xffffffffu;
+    auto load_labels = [&](int64_t slab_base, unsigned li) -> unsigned {
+        return (unsigned)*reinterpret_cast<const LabWord *>(c.prev + (slab_base + li) * R + lab_off);
+    };
     auto fetch = [&](int64_t slab_base) {
         const float *Xs = c.X + slab_base * c.ldx;
         const unsigned last = (unsigned)min((int64_t)(SLAB_ - 1), c.chunk_end - 1 - slab_base);
@@ -447,9 +509,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 for (int sl = 0; sl < NP; ++sl) pnext[pb][sl] = bp[sl * 64 + lane];
                 nnext[pb] = reinterpret_cast<const uint2 *>(bp + NP * 64)[n];
                 const unsigned li = min((unsigned)(pb * 32 + n), last);
-                const unsigned char *prev_slab = c.prev + slab_base;
-#pragma unroll
-                for (int st = 0; st < ST; ++st) oldn[pb][st] = (int)prev_slab[run_off[st] + li];
+                oldn[pb] = load_labels(slab_base, li);
             }
             return;
         }
@@ -468,11 +528,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 for (int s = 0; s < H; ++s) xnext[pb][s] = Xs[ro + foff[s]];
             }
             // labels these (point, run) pairs had in the previous round, 0xff before the first one
-            if (!FINAL) {
-                const unsigned char *prev_slab = c.prev + slab_base;
-#pragma unroll
-                for (int st = 0; st < ST; ++st) oldn[pb][st] = (int)prev_slab[run_off[st] + li];
-            }
+            if (!FINAL) oldn[pb] = load_labels(slab_base, li);
         }
     };
     // the outstanding loads of fetch() have to be complete here
@@ -493,9 +549,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         }
         if (!FINAL) {
 #pragma unroll
-            for (int pb = 0; pb < NB; ++pb)
-#pragma unroll
-                for (int st = 0; st < ST; ++st) asm volatile("" : "+v"(oldn[pb][st]));
+            for (int pb = 0; pb < NB; ++pb) asm volatile("" : "+v"(oldn[pb]));
         }
     };
     // The chunk is handed out in slabs of SLAB points: one per wave statically, the rest from a counter in
@@ -613,7 +667,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         bf16x8 bb[NB];
         float xn[NB];
         int m1[NB][ST], m2[NB][ST];
-        int oldl[NB][ST];                 // label in the previous round (read only for active pairs)
+        unsigned oldl[NB];                // labels in the previous round, one byte per run of this lane
+        auto old_of = [&](int pb, int st) -> int { return (int)((oldl[pb] >> (8 * st)) & 0xffu); };
         if constexpr (PRE) {
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb) {
@@ -625,10 +680,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 xn[pb] = (__uint_as_float(nnext[pb].x << 16) + __uint_as_float(nnext[pb].x & 0xffff0000u)) + __uint_as_float(nnext[pb].y << 16);
                 bb[pb] = hl ? as_bf16x8(make_uint4(nnext[pb].x, nnext[pb].y, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
 #pragma unroll
-                for (int st = 0; st < ST; ++st) {
-                    m1[pb][st] = kBigKey; m2[pb][st] = kBigKey;
-                    oldl[pb][st] = oldn[pb][st];
-                }
+                for (int st = 0; st < ST; ++st) { m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; }
+                oldl[pb] = oldn[pb];
             }
         } else {
 #pragma unroll
@@ -653,10 +706,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             split3(xn[pb], nh, nm, nl);
             bb[pb] = hl ? as_bf16x8(make_uint4(nh | (nm << 16), nl, 0u, 0u)) : as_bf16x8(make_uint4(0x3f803f80u, 0x3f80u, 0u, 0u));
 #pragma unroll
-            for (int st = 0; st < ST; ++st) {
-                m1[pb][st] = kBigKey; m2[pb][st] = kBigKey;
-                oldl[pb][st] = oldn[pb][st];        // fetched with the rows, a slab ago
-            }
+            for (int st = 0; st < ST; ++st) { m1[pb][st] = kBigKey; m2[pb][st] = kBigKey; }
+            oldl[pb] = oldn[pb];                    // fetched with the rows, a slab ago
         }
         }
 
@@ -745,31 +796,63 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             for (int st = 0; st < ST; ++st) {
                 const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
                 const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
-                const int k1 = m1[pb][st], k2 = m2[pb][st];
-                const float f1 = __int_as_float(k1 & (int)0xffffff80), f2 = __int_as_float(k2 & (int)0xffffff80);
-                // error bound of the two expansions (rounding of norms, products and the centring) plus the 7
-                // mantissa bits given up to the index: a key is its value cut down by less than 2^-16 of itself,
-                // so the smaller key's value may lie that much higher (2^-15 here)
+                // Error bound of the two expansions (rounding of norms, products and the centring) plus the 7
+                // mantissa bits given up to the index.  The keys are compared as they are, index bits included:
+                // read as a float a key g lies within 2^-16 |v| of the value v it was packed from, so
+                // v2 - v1 >= g2 (1 - 2^-15) - g1 whenever g2 >= |g1| - and a negative g1 (a distance of zero
+                // within the bound) is smaller than the bound's own slack.  One multiply-add and one compare.
+                const float g1 = __int_as_float(m1[pb][st]), g2 = __int_as_float(m2[pb][st]);
                 const float tol0 = fmaf(c.eps_a, xn[pb], tol_run[st]);
-                const bool close = active && !(f2 - f1 > fmaf(3.0517578125e-5f, fabsf(f2), tol0));
+                const bool close = active && !(fmaf(g2, 0.999969482421875f, -g1) > tol0);
                 pend |= (unsigned)close << (pb * ST + st);
             }
         }
 
+        // A close call (about one pair in a thousand on knob data; every pair where centroids coincide or integer
+        // data ties exactly) is settled by the whole wave with the exact arithmetic over the run.  The point's row is
+        // read out of the registers of the two lanes that hold its halves.
+        auto settle_close_calls = [&](const float (&xr)[NB][HP]) {
+            unsigned long long todo = __ballot(pend != 0u);
+            while (todo) {
+                const int src = __ffsll((long long)todo) - 1;
+                const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend, src);
+                const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
+                const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
+                const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * CS;
+                float xs[DP];
+#pragma unroll
+                for (int s = 0; s < H; ++s) {
+                    float v = xr[0][s];
+#pragma unroll
+                    for (int q = 1; q < NB; ++q)
+                        if (pb == q) v = xr[q][s];
+                    xs[s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src & 31));
+                    xs[H + s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), (src & 31) + 32));
+                }
+                const int arg = exact_argmin_wave<DP>(xs, crun, CS, c.k0 + srl);
+                if (lane == src) {
+                    pend &= pend - 1u;
+#pragma unroll
+                    for (int i = 0; i < NBST; ++i)
+                        if (i == idx) m1[i / ST][i % ST] = arg;
+                }
+                todo = __ballot(pend != 0u);
+            }
+        };
         if constexpr (PRE) {
             // Raw rows on demand: the exact arithmetic of a close call needs the point's row; both lanes of such a
             // point (each holds half of the features) load their half.  (The exact sums need the rows of the points
-            // whose label changed: those are read when the wave works off its log of moved pairs.)
-            unsigned need = pend;
-            need |= xchg32(need);
+            // whose label changed: those are read when the wave works off its log of moved pairs.)  Loads, wait and
+            // scans sit in one branch, so that a slab without close calls never waits on the memory counter here: what
+            // is in flight then are the operands of the next slab, wanted a whole slab later.
+            if (__ballot(pend != 0u) != 0ull) {
+                unsigned need = pend;
+                need |= xchg32(need);
+                float xr[NB][HP];
 #pragma unroll
-            for (int pb = 0; pb < NB; ++pb)
+                for (int pb = 0; pb < NB; ++pb)
 #pragma unroll
-                for (int s = 0; s < HP; ++s) {
-                    if (s < H) asm volatile("" : "=v"(xraw[pb][s]));     // defined, whatever it holds: read only where loaded
-                    else xraw[pb][s] = 0.0f;
-                }
-            if (__ballot(need != 0u) != 0ull) {
+                    for (int s = 0; s < HP; ++s) xr[pb][s] = 0.0f;
                 const float *Xs = c.X + base * c.ldx;
                 // (the row index is made opaque here so that the offsets below are worked out on the spot: hoisted out
                 // of the slab loop they would sit in registers, or in spill slots, through the tile loop)
@@ -783,67 +866,55 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                             for (int c4 = 0; c4 < H / 4; ++c4) {
                                 const float4 v = *reinterpret_cast<const float4 *>(Xs + (ro + feat_off(4 * c4)));
-                                xraw[pb][4 * c4 + 0] = v.x; xraw[pb][4 * c4 + 1] = v.y; xraw[pb][4 * c4 + 2] = v.z; xraw[pb][4 * c4 + 3] = v.w;
+                                xr[pb][4 * c4 + 0] = v.x; xr[pb][4 * c4 + 1] = v.y; xr[pb][4 * c4 + 2] = v.z; xr[pb][4 * c4 + 3] = v.w;
                             }
                         } else {
 #pragma unroll
-                            for (int s = 0; s < H; ++s) xraw[pb][s] = Xs[ro + feat_off(s)];
+                            for (int s = 0; s < H; ++s) xr[pb][s] = Xs[ro + feat_off(s)];
                         }
                         if (d < DP) {
 #pragma unroll
                             for (int s = 0; s < H; ++s)
-                                if (s >= nf) xraw[pb][s] = 0.0f;
+                                if (s >= nf) xr[pb][s] = 0.0f;
                         }
                     }
                 }
+                // the rows have to be there before the branch ends (the wait belongs to this path alone)
+#pragma unroll
+                for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                    for (int s = 0; s < H; ++s) asm volatile("" : "+v"(xr[pb][s]));
+                settle_close_calls(xr);
             }
+        } else {
+            settle_close_calls(xraw);
         }
 
-        // A close call (about one pair in a thousand on knob data; every pair where centroids coincide or integer
-        // data ties exactly) is settled by the whole wave with the exact arithmetic over the run.  The point's row is
-        // read out of the registers of the two lanes that hold its halves.
-        {
-            unsigned long long todo = __ballot(pend != 0u);
-            while (todo) {
-                const int src = __ffsll((long long)todo) - 1;
-                const unsigned sbits = (unsigned)__builtin_amdgcn_readlane((int)pend, src);
-                const int idx = __ffs(sbits) - 1, pb = idx / ST, st = idx % ST;
-                const int srl = S == 8 ? 0 : (src >> 5) * ST + st;
-                const float *crun = c.cs + (srl * c.k0 + srl * (srl - 1) / 2) * CS;
-                float xs[DP];
+        // labels are final: the new label word of every block, and which of its bytes differ from the last round's
+        // (the stores wait until the end of the slab)
+        unsigned neww[NB], diffw[NB];
+        unsigned mv = 0;                            // bit pb * ST + st: that pair moved
 #pragma unroll
-                for (int s = 0; s < H; ++s) {
-                    float v = xraw[0][s];
+        for (int pb = 0; pb < NB; ++pb) {
+            unsigned w = (unsigned)m1[pb][0] & 127u;
 #pragma unroll
-                    for (int q = 1; q < NB; ++q)
-                        if (pb == q) v = xraw[q][s];
-                    xs[s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src & 31));
-                    xs[H + s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), (src & 31) + 32));
-                }
-                const int arg = exact_argmin_wave<DP>(xs, crun, CS, c.k0 + srl);
-                if (lane == src) {
-                    pend &= pend - 1u;
-#pragma unroll
-                    for (int i = 0; i < NBST; ++i)
-                        if (i == idx) m1[i / ST][i % ST] = arg;
-                }
-                todo = __ballot(pend != 0u);
+            for (int st = 1; st < ST; ++st) w |= ((unsigned)m1[pb][st] & 127u) << (8 * st);
+            neww[pb] = w;
+            diffw[pb] = 0u;
+            if (!FINAL) {
+                const bool pvalid = base + pb * 32 + n < c.chunk_end;
+                diffw[pb] = pvalid ? ((w ^ oldl[pb]) & actmask) : 0u;
             }
         }
-
-        // labels are final: which pairs moved (the stores wait until the end of the slab)
-        unsigned mv = 0;
         if (!FINAL) {
+            bool any = false;
 #pragma unroll
-            for (int pb = 0; pb < NB; ++pb) {
-                const int64_t p = base + pb * 32 + n;
+            for (int pb = 0; pb < NB; ++pb) any = any || diffw[pb] != 0u;
+            if (__ballot(any) != 0ull) {
 #pragma unroll
-                for (int st = 0; st < ST; ++st) {
-                    const int rl = S == 8 ? 0 : hl * ST + st;
-                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
-                    const bool moved = active && (m1[pb][st] & 127) != oldl[pb][st];
-                    mv |= (unsigned)moved << (pb * ST + st);
-                }
+                for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                    for (int st = 0; st < ST; ++st) mv |= (unsigned)(((diffw[pb] >> (8 * st)) & 0xffu) != 0u) << (pb * ST + st);
             }
         }
 
@@ -865,7 +936,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                         const unsigned pt = (unsigned)(base - c.chunk_begin) + (unsigned)(pb * 32 + n);    // below 2^17
                         const unsigned rowbase = rl * (unsigned)c.k0 + rl * (rl - 1u) / 2u;
                         const unsigned lo = pt | ((rowbase + (unsigned)(m1[pb][st] & 127)) << 17);         // rows: below 2^12
-                        const unsigned hi = oldl[pb][st] == 0xff ? 0xffffu : rowbase + (unsigned)oldl[pb][st];
+                        const unsigned hi = old_of(pb, st) == 0xff ? 0xffffu : rowbase + (unsigned)old_of(pb, st);
                         c.log[pos & (kLogCap - 1)] = ((unsigned long long)hi << 32) | lo;
                     }
                     log_tail += (int)__popcll(bal);
@@ -936,7 +1007,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     int kk = 0;                         // the owner's (old << 8) | new
 #pragma unroll
                     for (int i = 0; i < NBST; ++i)
-                        if (i == idx) kk = (m1[i / ST][i % ST] & 127) | (oldl[i / ST][i % ST] << 8);
+                        if (i == idx) kk = (m1[i / ST][i % ST] & 127) | (old_of(i / ST, i % ST) << 8);
                     const int kko = xchg32(kk);
                     if (hl != oh) kk = kko;
                     const int nl = kk & 0xff, ol = kk >> 8;
@@ -1009,17 +1080,17 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
             const int64_t p = base + pb * 32 + n;
+            if (FINAL) {
 #pragma unroll
-            for (int st = 0; st < ST; ++st) {
-                const int rl = S == 8 ? 0 : hl * ST + st;
-                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
-                const int lab = m1[pb][st] & 127;
-                const unsigned off = run_off[st] + (unsigned)(pb * 32 + n);      // used for active pairs only: inside the chunk
-                if (FINAL) {
-                    if (active && c.labels_out) (c.labels_out + base)[off] = lab;
-                } else {
-                    if ((mv >> (pb * ST + st)) & 1u) (c.prev + base)[off] = (unsigned char)lab;
+                for (int st = 0; st < ST; ++st) {
+                    const int rl = S == 8 ? 0 : hl * ST + st;
+                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && p < c.chunk_end;
+                    const unsigned off = run_off[st] + (unsigned)(pb * 32 + n);      // used for active pairs only: inside the chunk
+                    if (active && c.labels_out) (c.labels_out + base)[off] = m1[pb][st] & 127;
                 }
+            } else {
+                // a word with a changed byte is written back whole (bytes of run slots without a run are never looked at)
+                if (diffw[pb] != 0u) *reinterpret_cast<LabWord *>(c.prev + p * R + lab_off) = (LabWord)neww[pb];
             }
         }
         cur = nxt;
@@ -1123,7 +1194,7 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     c.xp = reinterpret_cast<const uint4 *>(wsb + a.off_xp);
     c.log = reinterpret_cast<unsigned long long *>(wsb + a.off_log) + ((int64_t)blockIdx.x * WV + (tid >> 6)) * kLogCap;
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
-    c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.run0 * a.N;
+    c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.lab0 * ((a.N + 15) / 16 * 16);
     c.labels_out = (FINAL && a.labels) ? a.labels + (int64_t)b * a.lab_bs + (int64_t)g.run0 * a.N : nullptr;
     c.losum = reinterpret_cast<long long *>(wsb + a.off_losum);
     c.chunk_begin = (int64_t)chunk * plan.chunk_len;
@@ -1689,7 +1760,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     ia.off_opA = L.opA; ia.off_losum = L.losum; ia.off_tot = L.tot; ia.off_totcnt = L.totcnt; ia.off_prev = L.prev;
     ia.n_tiles = plan.total_tiles; ia.dp = DP;
     ia.n_losum = (int64_t)plan.total_rows * a.d; ia.n_tot = ia.n_losum * 2; ia.n_totcnt = ia.n_losum;
-    ia.n_prev16 = ((int64_t)plan.n_runs * a.N + 15) / 16;
+    ia.n_prev16 = (int64_t)plan.lab_slots * align_up(a.N, 16) / 16;
     hipLaunchKernelGGL(sweep_init_kernel, dim3(512, batch), dim3(256), 0, s, ia);
 
     CentroidArgs ca;
@@ -1776,6 +1847,7 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
     plan->n_groups = 0;
     int tiles = 0;
     int run = 0;
+    int lab_slots = 0;       // run slots (8 / S per group) of the groups so far
     while (run < plan->n_runs) {
         // candidates: R runs side by side (8 / R slots each); take the one with the least padding per real
         // row, preferring the larger R - except between candidates that cover the same runs at the same padding
@@ -1800,7 +1872,8 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
         if (best_R == 0 || plan->n_groups >= kMaxGroups) return RLS_ERR_INVALID_ARG;
         GroupDesc &g = plan->g[plan->n_groups++];
         g.run0 = (int16_t)run; g.n_runs = (int16_t)best_nr; g.S = (int16_t)(8 / best_R); g.n_tiles = (int16_t)best_tiles;
-        g.pad = 0; g.tile0 = tiles;
+        g.lab0 = (int16_t)lab_slots; g.tile0 = tiles;
+        lab_slots += best_R;
         // Runs with few clusters send many lanes of a wave to the same accumulator address (32 / k on average), which
         // the LDS works off one after the other: such groups keep several copies of their accumulators, LDS permitting.
         {
@@ -1814,6 +1887,7 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
         run += best_nr;
     }
     plan->total_tiles = tiles;
+    plan->lab_slots = lab_slots;
     // launch order: groups by falling cost (tiles per point)
     for (int i = 0; i < plan->n_groups; ++i) plan->sched[i] = (uint8_t)i;
     for (int i = 1; i < plan->n_groups; ++i) {
@@ -1866,7 +1940,7 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->losum = take((int64_t)plan.total_rows * d * 8);
     L->tot = take((int64_t)plan.total_rows * d * 16);
     L->totcnt = take((int64_t)plan.total_rows * d * 8);
-    L->prev = take(align_up((int64_t)plan.n_runs * N, 16));
+    L->prev = take((int64_t)plan.lab_slots * align_up(N, 16));
     L->xp = take((N + 31) / 32 * prep_block_u4_of(plan.dp) * 16);
     L->log = take((int64_t)plan.n_groups * plan.n_chunks * (step_threads_of(plan.dp) / 64) * kLogCap * 8);
     L->per_batch = off;

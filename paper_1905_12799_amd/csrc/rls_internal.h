@@ -36,7 +36,7 @@ struct GroupDesc {
     int16_t S;         // slots per run: 1, 2, 4 or 8
     int16_t n_tiles;   // 32-row tiles
     int16_t copies;    // copies of the LDS accumulators (a power of two up to 16)
-    int16_t pad;
+    int16_t lab0;      // run slots (8 / S each) of all earlier groups: where this group's label bytes begin, in units of N rounded up to 16
     int32_t tile0;     // tiles of all earlier groups (offset of this group's operand block)
 };
 
@@ -47,6 +47,7 @@ struct SweepPlan {
     int32_t n_runs;      // k_max - k_min + 1
     int32_t k_min;
     int32_t total_tiles;
+    int32_t lab_slots;   // sum over the groups of their 8 / S run slots
     int32_t total_rows;  // sum of k over the runs
     int32_t n_chunks;    // point chunks per group
     int32_t chunk_len;   // points per chunk (multiple of the tile size)
@@ -88,7 +89,7 @@ struct SweepLayout {
     int64_t losum;          // int64 [total_rows][d] low-order fixed-point sums of wide columns (running)
     int64_t tot;            // int64 [total_rows][d][2] running 128-bit fixed-point sums (hi, lo)
     int64_t totcnt;         // int64 [total_rows][d] running member counts (one copy per feature)
-    int64_t prev;           // uint8 [n_runs][N] label of every point in the last round (0xff: none yet)
+    int64_t prev;           // uint8 per group [N rounded up to 16][8 / S]: label of every point in the last round (0xff: none yet)
     int64_t log;            // uint64 [groups * chunks][waves][512] rings of moved-pair records, one per wave of the step kernel
     int64_t xp;             // prepared copy of the points: per block of 32, the matrix operands and squared norms (kmeans_lloyd.hip)
     int64_t per_batch;      // bytes per batch element (multiple of 256)
