@@ -49,32 +49,72 @@ __device__ inline double wave_inclusive_scan(double v)
     return v;
 }
 
-// D_i <- min(D_i, |x_i - c|^2) for the newest centre, plus one sum per block of kSeedBlock points
+// D_i <- min(D_i, |x_i - c|^2) for the newest centre, plus one sum per block of kSeedBlock points.
+// A thread owns points base + tid + 256 i; which thread sums which point, and in which order, never changes, so the
+// block sums are the same in every run.  When rows can be read 16 bytes at a time, 256 rows at a time travel through
+// LDS: consecutive lanes read consecutive 16 bytes of the row block (every cache line is fetched by one instruction;
+// a lane that walks its own row touches a line eight times, and with 256 lines per workgroup in flight the
+// first-level cache has dropped it in between), and each thread then reads its row back from LDS (rows of d + 4
+// floats: conflict free).  The rows of the next 256 points are requested before the arithmetic on the current ones.
+// Q: 16-byte units per row when rows can be read that way (d = 4 Q, aligned), 0: rows are read element by element.
+template <int Q>
 __global__ void __launch_bounds__(256) seed_update_kernel(const float *__restrict__ X, int64_t N, int d, int64_t ldx,
                                                          int64_t x_batch_stride, const int64_t *__restrict__ chain,
                                                          int64_t chain_batch_stride, int j, double *__restrict__ mind,
                                                          int64_t mind_batch_stride, double *__restrict__ bsum,
                                                          int64_t bsum_batch_stride)
 {
+    __shared__ __align__(16) float tile[Q > 0 ? 256 * (4 * Q + 4) : 4];
     __shared__ float cs[RLS_MAX_D];
     __shared__ double wsum[4];
     const int b = blockIdx.y;
     const float *Xb = X + (int64_t)b * x_batch_stride;
     double *D = mind + (int64_t)b * mind_batch_stride;
     const int64_t centre = chain[(int64_t)b * chain_batch_stride + (j - 1)];
-    const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && ((reinterpret_cast<uintptr_t>(Xb) & 15) == 0);
     if (threadIdx.x < d) cs[threadIdx.x] = Xb[centre * ldx + threadIdx.x];
-    __syncthreads();
     double local = 0.0;
     const int64_t base = (int64_t)blockIdx.x * kSeedBlock;
-    for (int i = 0; i < kSeedBlock / 256; ++i) {
-        const int64_t p = base + threadIdx.x + 256 * i;
-        if (p < N) {
-            const float *x = Xb + p * ldx;
-            double acc = 0.0;
-            if (vec) {
-                // same sum, the row read 16 bytes at a time
-                for (int l = 0; l < d; l += 4) {
+    constexpr int kIter = kSeedBlock / 256;
+    if constexpr (Q > 0) {
+        constexpr int q = Q;                         // 16-byte units per row
+        constexpr int rs = 4 * Q + 4;                // row stride of the tile, in floats
+        constexpr int kMaxQ = Q;
+        float stage[kMaxQ][4];
+        // unit u = tid + 256 e of a row block is 16 bytes of row u / q at feature 4 (u % q); rows past the end of the
+        // data are clamped to the last row (read, never used)
+        int urow[kMaxQ], ucol[kMaxQ];
+#pragma unroll
+        for (int e = 0; e < kMaxQ; ++e) {
+            const int u = (int)threadIdx.x + 256 * e;
+            urow[e] = u / q;
+            ucol[e] = 4 * (u % q);
+        }
+        // (written out with constant indices: the staged rows stay in registers)
+#define RLS_SEED_REQUEST(I)                                                                                              \
+    do {                                                                                                                 \
+        const int64_t row0_ = base + 256 * (I);                                                                          \
+        _Pragma("unroll") for (int e = 0; e < kMaxQ; ++e) {                                                              \
+            const float4 v_ = *reinterpret_cast<const float4 *>(Xb + min(row0_ + urow[e], N - 1) * ldx + ucol[e]);       \
+            stage[e][0] = v_.x; stage[e][1] = v_.y; stage[e][2] = v_.z; stage[e][3] = v_.w;                              \
+        }                                                                                                                \
+    } while (0)
+        RLS_SEED_REQUEST(0);
+#pragma unroll
+        for (int i = 0; i < kIter; ++i) {
+            if (base + 256 * i >= N) break;          // same for the whole workgroup
+            __syncthreads();                         // the tile is free (and, the first time, cs is there)
+#pragma unroll
+            for (int e = 0; e < kMaxQ; ++e) {
+                *reinterpret_cast<float4 *>(tile + urow[e] * rs + ucol[e]) = make_float4(stage[e][0], stage[e][1], stage[e][2], stage[e][3]);
+            }
+            if (i + 1 < kIter && base + 256 * (i + 1) < N) RLS_SEED_REQUEST(i + 1);
+            __syncthreads();
+            const int64_t p = base + threadIdx.x + 256 * i;
+            if (p < N) {
+                const float *x = tile + threadIdx.x * rs;
+                double acc = 0.0;
+#pragma unroll
+                for (int l = 0; l < 4 * Q; l += 4) {
                     const float4 xv = *reinterpret_cast<const float4 *>(x + l);
                     double diff = __dsub_rn((double)xv.x, (double)cs[l]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
@@ -85,19 +125,35 @@ __global__ void __launch_bounds__(256) seed_update_kernel(const float *__restric
                     diff = __dsub_rn((double)xv.w, (double)cs[l + 3]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
-            } else {
+                double cur = acc;
+                if (j > 1) {
+                    const double old = D[p];
+                    cur = acc < old ? acc : old;
+                }
+                D[p] = cur;
+                local = __dadd_rn(local, cur);
+            }
+        }
+#undef RLS_SEED_REQUEST
+    } else {
+        __syncthreads();
+        for (int i = 0; i < kIter; ++i) {
+            const int64_t p = base + threadIdx.x + 256 * i;
+            if (p < N) {
+                const float *x = Xb + p * ldx;
+                double acc = 0.0;
                 for (int l = 0; l < d; ++l) {
                     const double diff = __dsub_rn((double)x[l], (double)cs[l]);
                     acc = __dadd_rn(acc, __dmul_rn(diff, diff));
                 }
+                double cur = acc;
+                if (j > 1) {
+                    const double old = D[p];
+                    cur = acc < old ? acc : old;
+                }
+                D[p] = cur;
+                local = __dadd_rn(local, cur);
             }
-            double cur = acc;
-            if (j > 1) {
-                const double old = D[p];
-                cur = acc < old ? acc : old;
-            }
-            D[p] = cur;
-            local = __dadd_rn(local, cur);
         }
     }
     // block sum in fixed order: wave butterfly-free reduction via scan's last lane, then 4 waves in order
@@ -225,11 +281,27 @@ hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, 
         for (int i = 0; i < 64; ++i) sl.seed[i] = seeds_host[b0 + (i < nb ? i : 0)];
         if (j_begin == 0) hipLaunchKernelGGL(seed_first_kernel, dim3(nb), dim3(64), 0, s, sl, b0, N, chain, chain_batch_stride);
         for (int j = j_begin > 1 ? j_begin : 1; j < k_max; ++j) {
-            hipLaunchKernelGGL(seed_update_kernel, dim3(seed_blocks, nb), dim3(256), 0, s,
-                               X + (int64_t)b0 * x_batch_stride, N, (int)d, ldx, x_batch_stride,
-                               chain + (int64_t)b0 * chain_batch_stride, chain_batch_stride, j,
-                               mind + (int64_t)b0 * mind_batch_stride, mind_batch_stride,
-                               bsum + (int64_t)b0 * bsum_batch_stride, bsum_batch_stride);
+            const float *Xg = X + (int64_t)b0 * x_batch_stride;
+            // rows 16 bytes at a time when every space's rows allow it
+            const bool vec = (d % 4 == 0) && (ldx % 4 == 0) && (x_batch_stride % 4 == 0 || nb == 1) &&
+                             ((reinterpret_cast<uintptr_t>(Xg) & 15) == 0);
+#define RLS_SEED_UPDATE(QV)                                                                                              \
+    hipLaunchKernelGGL(seed_update_kernel<QV>, dim3(seed_blocks, nb), dim3(256), 0, s, Xg, N, (int)d, ldx,                \
+                       x_batch_stride, chain + (int64_t)b0 * chain_batch_stride, chain_batch_stride, j,                   \
+                       mind + (int64_t)b0 * mind_batch_stride, mind_batch_stride,                                         \
+                       bsum + (int64_t)b0 * bsum_batch_stride, bsum_batch_stride)
+            switch (vec ? d / 4 : 0) {
+            case 1: RLS_SEED_UPDATE(1); break;
+            case 2: RLS_SEED_UPDATE(2); break;
+            case 3: RLS_SEED_UPDATE(3); break;
+            case 4: RLS_SEED_UPDATE(4); break;
+            case 5: RLS_SEED_UPDATE(5); break;
+            case 6: RLS_SEED_UPDATE(6); break;
+            case 7: RLS_SEED_UPDATE(7); break;
+            case 8: RLS_SEED_UPDATE(8); break;
+            default: RLS_SEED_UPDATE(0); break;
+            }
+#undef RLS_SEED_UPDATE
             hipLaunchKernelGGL(seed_pick_kernel, dim3(nb), dim3(1024), 0, s, sl, b0, N, j, (int)seed_blocks, mind,
                                mind_batch_stride, bsum, bsum_batch_stride, chain, chain_batch_stride);
         }
