@@ -7,6 +7,7 @@
 // values to its own fp32 running sum in tree order, which makes the result independent of the launch shape.
 // A step of the walk is two dependent LDS reads and four vector instructions: the walk keeps the node's LDS
 // address a (node n of a tree at byte b sits at b + 8 n) and moves to child 2n + 1 + c by a <- 2 a + (8 + 8 c - b).
+#include <algorithm>
 #include <mutex>
 
 #include "rls_internal.h"
@@ -21,6 +22,14 @@ constexpr int kForestChunkBytes = 96 * 1024;   // with the 64 KB tile of configu
 // bytes), so the launcher also caps the trees per chunk by kStage * threads leaves.
 constexpr int kStage = (kForestChunkBytes / 12 + 511) / 512 + 1;
 
+// LDS is addressed by 32-bit byte addresses that the walk computes itself (the start of the dynamic block is folded into
+// them once: as a pointer offset it is a link-time constant and would cost an addition per read)
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+__device__ inline unsigned lds_address(const void *p) { return (unsigned)(uintptr_t)(lds_byte *)p; }
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+__device__ inline uint2v lds_read_u2(unsigned a) { return *(const __attribute__((address_space(3))) uint2v *)(uintptr_t)a; }
+__device__ inline float lds_read_f(unsigned a) { return *(const __attribute__((address_space(3))) float *)(uintptr_t)a; }
+
 __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int64_t N, int d, int64_t ldx,
                                  float *__restrict__ score, int trees_per_chunk)
 {
@@ -33,6 +42,7 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
     float *leaves = reinterpret_cast<float *>(nodes + (size_t)trees_per_chunk * n_int);   // [trees_per_chunk][n_leaf]
 
     const int tid = threadIdx.x;
+    const unsigned lds0 = lds_address(smem);
     const int64_t row = (int64_t)blockIdx.x * P + tid;
     const bool valid = row < N;
     {
@@ -73,7 +83,7 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
             const int e = tid + i * P;
             if (e < n_nodes) {
                 const int ft = min(max(st_feat[i], 0), d - 1);
-                nodes[e] = make_uint2((unsigned)ft * (unsigned)P * 4u, __float_as_uint(st_thr[i]));
+                nodes[e] = make_uint2(lds0 + (unsigned)ft * (unsigned)P * 4u, __float_as_uint(st_thr[i]));
             }
             if (e < n_leaves) leaves[e] = st_leaf[i];
         }
@@ -85,13 +95,15 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
     __syncthreads();   // first chunk and xs in place
     for (int t0 = 0; t0 < f.n_trees; t0 += trees_per_chunk) {
         const int tc = min(trees_per_chunk, f.n_trees - t0);
+        const int tc_cap = trees_per_chunk;
         const int t_next = t0 + trees_per_chunk;
         const int tc_next = min(trees_per_chunk, f.n_trees - t_next);
         if (tc_next > 0) fetch_chunk(t_next, tc_next);
         // Four trees are walked side by side: a walk is a chain of dependent LDS reads (node, then feature value),
         // and independent chains keep more of them in flight.  The leaves are still added in tree order.
         constexpr int W = 4;
-        const unsigned nodes_at = (unsigned)((size_t)d * P * 4);        // byte offset of the node block in LDS
+        const unsigned nodes_at = lds0 + (unsigned)((size_t)d * P * 4);        // LDS address of the node block
+        const unsigned leaves_at = nodes_at + (unsigned)tc_cap * (unsigned)n_int * 8u;
         const unsigned tid4 = (unsigned)tid * 4u;
         for (int t = 0; t < tc; t += W) {
             unsigned base[W], a[W], k_left[W], k_right[W];
@@ -104,18 +116,20 @@ __global__ void gbt_score_kernel(ForestArgs f, const float *__restrict__ X, int6
                 asm volatile("" : "+v"(k_left[w]), "+v"(k_right[w]));   // keep both as they are: one select per step
             }
             for (int lev = 0; lev < f.depth; ++lev) {
-                uint2 nd[W];
+                uint2v nd[W];
 #pragma unroll
-                for (int w = 0; w < W; ++w) nd[w] = *reinterpret_cast<const uint2 *>(smem + a[w]);
+                for (int w = 0; w < W; ++w) nd[w] = lds_read_u2(a[w]);
                 float xv[W];
 #pragma unroll
-                for (int w = 0; w < W; ++w) xv[w] = *reinterpret_cast<const float *>(smem + (nd[w].x + tid4));
+                for (int w = 0; w < W; ++w) xv[w] = lds_read_f(nd[w].x + tid4);
 #pragma unroll
                 for (int w = 0; w < W; ++w) a[w] = 2u * a[w] + ((xv[w] < __uint_as_float(nd[w].y)) ? k_left[w] : k_right[w]);
             }
+            // leaf l of tree t + w: the walk ends at a = base + 8 (n_int + l), the leaf sits at leaves_at + 4 ((t + w) n_leaf + l)
+            // = a / 2 + (leaves_at + 4 (t + w) n_leaf - 4 n_int - base / 2): one shift and one add of a scalar
 #pragma unroll
             for (int w = 0; w < W; ++w)
-                if (t + w < tc) sum = sum + leaves[(t + w) * n_leaf + (int)((a[w] - base[w]) >> 3) - n_int];
+                if (t + w < tc) sum = sum + lds_read_f((a[w] >> 1) + (leaves_at + 4u * (unsigned)((t + w) * n_leaf - n_int) - (base[w] >> 1)));
         }
         __syncthreads();   // every wave is done with this chunk
         if (tc_next > 0) store_chunk(tc_next);
@@ -140,7 +154,9 @@ hipError_t launch_gbt_score(const ForestArgs *forests_host, int32_t batch, const
     for (int32_t b = 0; b < batch; ++b) {
         const ForestArgs &f = forests_host[b];
         const int64_t tree_bytes = (((int64_t)1 << f.depth) - 1) * 8 + ((int64_t)1 << f.depth) * 4;
-        int tpc = (int)(kForestChunkBytes / tree_bytes);
+        // the forest chunk takes what the tile of configurations leaves of the 160 KB, at most kForestChunkBytes
+        const int64_t chunk_bytes = std::min<int64_t>(kForestChunkBytes, 160 * 1024 - (int64_t)d * P * 4);
+        int tpc = (int)(chunk_bytes / tree_bytes);
         // a thread stages kStage entries of the next chunk: its leaves (the larger of the two arrays) must fit
         const int64_t stage_cap = ((int64_t)kStage * P) >> f.depth;
         if (tpc > stage_cap) tpc = (int)stage_cap;
