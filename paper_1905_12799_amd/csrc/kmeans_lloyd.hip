@@ -725,54 +725,111 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             for (int sl = 0; sl < NS; ++sl) dst[sl] = opA_s[(t * NS + sl) * 64 + lane];
         };
         load_a(a_even, 0);
-        floatx16 acc_prev;                 // results of the block before the current one, folded one block late
-        int kidx_old[16];
-        // `first`: the very first block of the slab has no block before it to fold
-        auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto first) {
-            load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
-            // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
-            int kidx[16];
+        if constexpr (NB == 1 && NK == 1) {
+            // One block per slab: the four MFMAs of a tile form one dependent chain, so the wave interleaves them in
+            // program order with the fold of the tile before - a quarter of the fold (one quad of rows) behind each MFMA -
+            // and the two accumulators alternate by name.  The order is pinned: left to itself the compiler folds first
+            // and then issues the chain into the same registers, and nothing of the wave overlaps.
+            floatx16 acc_a, acc_b;
+            int kidx_prev[16];
+            auto fold_quad = [&](const floatx16 &acc, const int (&kidx)[16], int q) {
+                const int st = state_of<S>(q);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                kidx[e] = key_index<S>(t, e >> 2, e & 3);
-                asm("" : "+s"(kidx[e]));
-            }
+                for (int i = 0; i < 4; i += 2)
+                    insert2x2(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), pack_key(acc[4 * q + i + 1], mask, kidx[4 * q + i + 1]),
+                              m1[0][st], m2[0][st]);
+            };
+            auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto first, floatx16 &acc_new, const floatx16 &acc_old) {
+                load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
+                int kidx[16];
 #pragma unroll
-            for (int pb = 0; pb < NB; ++pb) {
-                // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
-                floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // l.h
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][1][ks], acc, 0, 0, 0);   // h.l
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // h.h
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2 * NK]), bb[pb], acc, 0, 0, 0);                                         // norms
-                if (pb == 0) {
-                    if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
-                } else {
-                    fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1]);
+                for (int e = 0; e < 16; ++e) {
+                    kidx[e] = key_index<S>(t, e >> 2, e & 3);
+                    asm("" : "+s"(kidx[e]));
                 }
+                constexpr bool kFold = !decltype(first)::value;
+                const floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1]), bx[0][0][0], zero, 0, 0, 0);        // l.h
+                __builtin_amdgcn_sched_barrier(0);
+                if (kFold) fold_quad(acc_old, kidx_prev, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][1][0], acc_new, 0, 0, 0);     // h.l
+                __builtin_amdgcn_sched_barrier(0);
+                if (kFold) fold_quad(acc_old, kidx_prev, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][0][0], acc_new, 0, 0, 0);     // h.h
+                __builtin_amdgcn_sched_barrier(0);
+                if (kFold) fold_quad(acc_old, kidx_prev, 2);
+                __builtin_amdgcn_sched_barrier(0);
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2]), bb[0], acc_new, 0, 0, 0);         // norms
+                __builtin_amdgcn_sched_barrier(0);
+                if (kFold) fold_quad(acc_old, kidx_prev, 3);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int s = 0; s < NM; ++s) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);   // then a share of the fold
-                }
-                acc_prev = acc;
-            }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
-        };
-        {
-            tile_step(a_even, a_odd, 0, std::true_type{});
+                for (int e = 0; e < 16; ++e) kidx_prev[e] = kidx[e];
+            };
+            tile_step(a_even, a_odd, 0, std::true_type{}, acc_a, acc_b);
             int t = 1;
             for (; t + 2 <= c.n_tiles; t += 2) {
-                tile_step(a_odd, a_even, t, std::false_type{});
-                tile_step(a_even, a_odd, t + 1, std::false_type{});
+                tile_step(a_odd, a_even, t, std::false_type{}, acc_b, acc_a);
+                tile_step(a_even, a_odd, t + 1, std::false_type{}, acc_a, acc_b);
             }
-            if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
+            if (t < c.n_tiles) {
+                tile_step(a_odd, a_even, t, std::false_type{}, acc_b, acc_a);
+                fold_tile<S, ST>(acc_b, kidx_prev, mask, m1[0], m2[0]);
+            } else {
+                fold_tile<S, ST>(acc_a, kidx_prev, mask, m1[0], m2[0]);
+            }
+        } else {
+        floatx16 acc_prev;                 // results of the block before the current one, folded one block late
+            int kidx_old[16];
+            // `first`: the very first block of the slab has no block before it to fold
+            auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto first) {
+                load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
+                // per-row key indices of this tile as opaque scalars (one scalar operand per and-or)
+                int kidx[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    kidx[e] = key_index<S>(t, e >> 2, e & 3);
+                    asm("" : "+s"(kidx[e]));
+                }
+#pragma unroll
+                for (int pb = 0; pb < NB; ++pb) {
+                    // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator
+                    floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // l.h
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][1][ks], acc, 0, 0, 0);   // h.l
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0 * NK + ks]), bx[pb][0][ks], acc, 0, 0, 0);   // h.h
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2 * NK]), bb[pb], acc, 0, 0, 0);                                         // norms
+                    if (pb == 0) {
+                        if (!decltype(first)::value) fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
+                    } else {
+                        fold_tile<S, ST>(acc_prev, kidx, mask, m1[pb - 1], m2[pb - 1]);
+                    }
+#pragma unroll
+                    for (int s = 0; s < NM; ++s) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, VPER, 0);   // then a share of the fold
+                    }
+                    acc_prev = acc;
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) kidx_old[e] = kidx[e];
+            };
+            {
+                tile_step(a_even, a_odd, 0, std::true_type{});
+                int t = 1;
+                for (; t + 2 <= c.n_tiles; t += 2) {
+                    tile_step(a_odd, a_even, t, std::false_type{});
+                    tile_step(a_even, a_odd, t + 1, std::false_type{});
+                }
+                if (t < c.n_tiles) tile_step(a_odd, a_even, t, std::false_type{});
+            }
+            fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
         }
-        fold_tile<S, ST>(acc_prev, kidx_old, mask, m1[NB - 1], m2[NB - 1]);
         if (LATE_FETCH) fetch(c.chunk_begin + (int64_t)min(nxt, n_slabs - 1) * SLAB);
 
         // ---- labels, close calls, sums
