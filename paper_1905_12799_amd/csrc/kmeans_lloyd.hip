@@ -494,8 +494,11 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         if (((S == 8) ? (hl == 0) : true) && (int)rl < c.n_runs) actmask |= 0xffu << (8 * st);
     }
     for (int pb = 0; pb < NB; ++pb) oldn[pb] = 0xffffffffu;
+    unsigned char *const prev_chunk = c.prev + c.chunk_begin * R;          // the chunk's first label byte
+    const unsigned chunk_pts = (unsigned)(c.chunk_end - c.chunk_begin);   // points of the chunk (at most 2^17)
     auto load_labels = [&](int64_t slab_base, unsigned li) -> unsigned {
-        return (unsigned)*reinterpret_cast<const LabWord *>(c.prev + (slab_base + li) * R + lab_off);
+        const unsigned pt = (unsigned)(slab_base - c.chunk_begin) + li;   // point within the chunk
+        return (unsigned)*reinterpret_cast<const LabWord *>(prev_chunk + (pt * (unsigned)R + lab_off));
     };
     auto fetch = [&](int64_t slab_base) {
         const float *Xs = c.X + slab_base * c.ldx;
@@ -732,14 +735,23 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             // and then issues the chain into the same registers, and nothing of the wave overlaps.
             floatx16 acc_a, acc_b;
             int kidx_prev[16];
-            auto fold_quad = [&](const floatx16 &acc, const int (&kidx)[16], int q) {
+            // `init`: the first tile of a slab - the first two keys of a run start its pair of smallest keys outright
+            // (no sentinel values to set up and compare against)
+            auto fold_quad = [&](const floatx16 &acc, const int (&kidx)[16], int q, auto init) {
                 const int st = state_of<S>(q);
-#pragma unroll
-                for (int i = 0; i < 4; i += 2)
-                    insert2x2(pack_key(acc[4 * q + i], mask, kidx[4 * q + i]), pack_key(acc[4 * q + i + 1], mask, kidx[4 * q + i + 1]),
-                              m1[0][st], m2[0][st]);
+                const bool starts = decltype(init)::value && (S == 1 || (S == 2 && (q & 1) == 0) || (S >= 4 && q == 0));
+                const int ka = pack_key(acc[4 * q], mask, kidx[4 * q]), kb = pack_key(acc[4 * q + 1], mask, kidx[4 * q + 1]);
+                if (starts) {
+                    m1[0][st] = min(ka, kb);
+                    m2[0][st] = max(ka, kb);
+                } else {
+                    insert2x2(ka, kb, m1[0][st], m2[0][st]);
+                }
+                insert2x2(pack_key(acc[4 * q + 2], mask, kidx[4 * q + 2]), pack_key(acc[4 * q + 3], mask, kidx[4 * q + 3]),
+                          m1[0][st], m2[0][st]);
             };
-            auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto first, floatx16 &acc_new, const floatx16 &acc_old) {
+            // `fold`: 0 nothing to fold (first tile), 1 the tile before is the slab's first, 2 any later tile
+            auto tile_step = [&](const uint4 (&a_cur)[NS], uint4 (&a_nxt)[NS], int t, auto fold, floatx16 &acc_new, const floatx16 &acc_old) {
                 load_a(a_nxt, t + 1 < c.n_tiles ? t + 1 : t);
                 int kidx[16];
 #pragma unroll
@@ -747,38 +759,48 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     kidx[e] = key_index<S>(t, e >> 2, e & 3);
                     asm("" : "+s"(kidx[e]));
                 }
-                constexpr bool kFold = !decltype(first)::value;
+                constexpr int kFold = decltype(fold)::value;
+                using Init = std::integral_constant<bool, kFold == 1>;
                 const floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
                 acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1]), bx[0][0][0], zero, 0, 0, 0);        // l.h
                 __builtin_amdgcn_sched_barrier(0);
-                if (kFold) fold_quad(acc_old, kidx_prev, 0);
+                if (kFold) fold_quad(acc_old, kidx_prev, 0, Init{});
                 __builtin_amdgcn_sched_barrier(0);
                 acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][1][0], acc_new, 0, 0, 0);     // h.l
                 __builtin_amdgcn_sched_barrier(0);
-                if (kFold) fold_quad(acc_old, kidx_prev, 1);
+                if (kFold) fold_quad(acc_old, kidx_prev, 1, Init{});
                 __builtin_amdgcn_sched_barrier(0);
                 acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][0][0], acc_new, 0, 0, 0);     // h.h
                 __builtin_amdgcn_sched_barrier(0);
-                if (kFold) fold_quad(acc_old, kidx_prev, 2);
+                if (kFold) fold_quad(acc_old, kidx_prev, 2, Init{});
                 __builtin_amdgcn_sched_barrier(0);
                 acc_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2]), bb[0], acc_new, 0, 0, 0);         // norms
                 __builtin_amdgcn_sched_barrier(0);
-                if (kFold) fold_quad(acc_old, kidx_prev, 3);
+                if (kFold) fold_quad(acc_old, kidx_prev, 3, Init{});
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) kidx_prev[e] = kidx[e];
             };
-            tile_step(a_even, a_odd, 0, std::true_type{}, acc_a, acc_b);
-            int t = 1;
-            for (; t + 2 <= c.n_tiles; t += 2) {
-                tile_step(a_odd, a_even, t, std::false_type{}, acc_b, acc_a);
-                tile_step(a_even, a_odd, t + 1, std::false_type{}, acc_a, acc_b);
-            }
-            if (t < c.n_tiles) {
-                tile_step(a_odd, a_even, t, std::false_type{}, acc_b, acc_a);
-                fold_tile<S, ST>(acc_b, kidx_prev, mask, m1[0], m2[0]);
+            using NoFold = std::integral_constant<int, 0>;
+            using FoldFirst = std::integral_constant<int, 1>;
+            using FoldLater = std::integral_constant<int, 2>;
+            tile_step(a_even, a_odd, 0, NoFold{}, acc_a, acc_b);
+            if (c.n_tiles == 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) fold_quad(acc_a, kidx_prev, q, std::true_type{});
             } else {
-                fold_tile<S, ST>(acc_a, kidx_prev, mask, m1[0], m2[0]);
+                tile_step(a_odd, a_even, 1, FoldFirst{}, acc_b, acc_a);
+                int t = 2;
+                for (; t + 2 <= c.n_tiles; t += 2) {
+                    tile_step(a_even, a_odd, t, FoldLater{}, acc_a, acc_b);
+                    tile_step(a_odd, a_even, t + 1, FoldLater{}, acc_b, acc_a);
+                }
+                if (t < c.n_tiles) {
+                    tile_step(a_even, a_odd, t, FoldLater{}, acc_a, acc_b);
+                    fold_tile<S, ST>(acc_a, kidx_prev, mask, m1[0], m2[0]);
+                } else {
+                    fold_tile<S, ST>(acc_b, kidx_prev, mask, m1[0], m2[0]);
+                }
             }
         } else {
         floatx16 acc_prev;                 // results of the block before the current one, folded one block late
@@ -834,11 +856,22 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 
         // ---- labels, close calls, sums
         constexpr int NBST = NB * ST;               // (block, run) pairs a lane owns
-        // Keys: which pairs does the exact arithmetic have to confirm?  Bit pb * ST + st of a lane's mask.
-        unsigned pend = 0;
+        // this lane's points within the chunk, and whether they exist (the last slab of a chunk may be ragged)
+        const unsigned pt0 = (unsigned)(base - c.chunk_begin);
+        unsigned ptl[NB];
+        bool pvalid[NB];
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            const bool pvalid = base + pb * 32 + n < c.chunk_end;
+            ptl[pb] = pt0 + (unsigned)(pb * 32 + n);
+            pvalid[pb] = ptl[pb] < chunk_pts;
+        }
+        // Keys: which pairs does the exact arithmetic have to confirm?  Bit pb * ST + st of a lane's mask, put together
+        // only when the wave has such a pair at all.
+        unsigned pend = 0;
+        bool closeb[NB][ST];
+        bool any_close = false;
+#pragma unroll
+        for (int pb = 0; pb < NB; ++pb) {
             if (S == 8) {
                 // the run spans both half-waves: add the half bit to the index, then merge with the partner lane
                 int k1 = m1[pb][0], k2 = m2[pb][0];
@@ -852,7 +885,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
             for (int st = 0; st < ST; ++st) {
                 const int rl = S == 8 ? 0 : hl * ST + st;     // run within the group
-                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
+                const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid[pb];
                 // Error bound of the two expansions (rounding of norms, products and the centring) plus the 7
                 // mantissa bits given up to the index.  The keys are compared as they are, index bits included:
                 // read as a float a key g lies within 2^-16 |v| of the value v it was packed from, so
@@ -860,9 +893,15 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 // within the bound) is smaller than the bound's own slack.  One multiply-add and one compare.
                 const float g1 = __int_as_float(m1[pb][st]), g2 = __int_as_float(m2[pb][st]);
                 const float tol0 = fmaf(c.eps_a, xn[pb], tol_run[st]);
-                const bool close = active && !(fmaf(g2, 0.999969482421875f, -g1) > tol0);
-                pend |= (unsigned)close << (pb * ST + st);
+                closeb[pb][st] = active && !(fmaf(g2, 0.999969482421875f, -g1) > tol0);
+                any_close = any_close || closeb[pb][st];
             }
+        }
+        if (__ballot(any_close) != 0ull) {
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb)
+#pragma unroll
+                for (int st = 0; st < ST; ++st) pend |= (unsigned)closeb[pb][st] << (pb * ST + st);
         }
 
         // A close call (about one pair in a thousand on knob data; every pair where centroids coincide or integer
@@ -953,15 +992,19 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         unsigned mv = 0;                            // bit pb * ST + st: that pair moved
 #pragma unroll
         for (int pb = 0; pb < NB; ++pb) {
-            unsigned w = (unsigned)m1[pb][0] & 127u;
-#pragma unroll
-            for (int st = 1; st < ST; ++st) w |= ((unsigned)m1[pb][st] & 127u) << (8 * st);
+            // the low bytes of the keys side by side (byte permutes), index bits only
+            unsigned w;
+            if constexpr (ST == 4) {
+                w = (__builtin_amdgcn_perm((unsigned)m1[pb][1], (unsigned)m1[pb][0], 0x0c0c0400u) |
+                     __builtin_amdgcn_perm((unsigned)m1[pb][3], (unsigned)m1[pb][2], 0x04000c0cu)) & 0x7f7f7f7fu;
+            } else if constexpr (ST == 2) {
+                w = __builtin_amdgcn_perm((unsigned)m1[pb][1], (unsigned)m1[pb][0], 0x0c0c0400u) & 0x7f7fu;
+            } else {
+                w = (unsigned)m1[pb][0] & 127u;
+            }
             neww[pb] = w;
             diffw[pb] = 0u;
-            if (!FINAL) {
-                const bool pvalid = base + pb * 32 + n < c.chunk_end;
-                diffw[pb] = pvalid ? ((w ^ oldl[pb]) & actmask) : 0u;
-            }
+            if (!FINAL) diffw[pb] = pvalid[pb] ? ((w ^ oldl[pb]) & actmask) : 0u;
         }
         if (!FINAL) {
             bool any = false;
@@ -990,7 +1033,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                     if (has) {
                         // the record names the point and the two accumulator rows (within the group) outright, so
                         // that working it off takes no arithmetic on runs and labels
-                        const unsigned pt = (unsigned)(base - c.chunk_begin) + (unsigned)(pb * 32 + n);    // below 2^17
+                        const unsigned pt = ptl[pb];                                                       // below 2^17
                         const unsigned rowbase = rl * (unsigned)c.k0 + rl * (rl - 1u) / 2u;
                         const unsigned lo = pt | ((rowbase + (unsigned)(m1[pb][st] & 127)) << 17);         // rows: below 2^12
                         const unsigned hi = old_of(pb, st) == 0xff ? 0xffffu : rowbase + (unsigned)old_of(pb, st);
@@ -1037,7 +1080,6 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                     for (int pb = 0; pb < NB; ++pb) {
                         const int64_t p = base + pb * 32 + n;
-                        const bool pvalid = p < c.chunk_end;
                         for (int r = 0; r < c.n_runs; ++r) {
                             const int oh = S == 8 ? 0 : r / ST, ost = S == 8 ? 0 : r % ST;
                             int nl = 0;
@@ -1047,7 +1089,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                             const int nlo = xchg32(nl);
                             if (hl != oh) nl = nlo;
                             const int rowbase = r * c.k0 + r * (r - 1) / 2;
-                            if (pvalid) {
+                            if (pvalid[pb]) {
                                 unsigned long long *sn = sums_l + (rowbase + nl) * (DP + 1) + f0;
 #pragma unroll
                                 for (int s = 0; s < H; ++s) atomicAdd(sn + s, fx[pb][s]);
@@ -1100,7 +1142,6 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             // partner lane by register swap.  Padded features are zero on both sides and add +0.
 #pragma unroll
             for (int pb = 0; pb < NB; ++pb) {
-                const bool pvalid = base + pb * 32 + n < c.chunk_end;
                 float xf[DP];
 #pragma unroll
                 for (int s = 0; s < H; ++s) {
@@ -1111,7 +1152,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
 #pragma unroll
                 for (int st = 0; st < ST; ++st) {
                     const int rl = S == 8 ? 0 : hl * ST + st;
-                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid;
+                    const bool active = ((S == 8) ? (hl == 0) : true) && rl < c.n_runs && pvalid[pb];
                     const int row = active ? rl * c.k0 + rl * (rl - 1) / 2 + (m1[pb][st] & 127) : 0;
                     const float *crow = c.cs + row * CS;
                     double dist = 0.0;
@@ -1147,7 +1188,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 }
             } else {
                 // a word with a changed byte is written back whole (bytes of run slots without a run are never looked at)
-                if (diffw[pb] != 0u) *reinterpret_cast<LabWord *>(c.prev + p * R + lab_off) = (LabWord)neww[pb];
+                if (diffw[pb] != 0u) *reinterpret_cast<LabWord *>(prev_chunk + (ptl[pb] * (unsigned)R + lab_off)) = (LabWord)neww[pb];
             }
         }
         cur = nxt;
