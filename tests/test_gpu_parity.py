@@ -451,7 +451,8 @@ def test_sweep_wide_columns(rls, orc):
     assert compare_sweep(orc, X, res, ref, 1, 9) == 0
 
 
-@pytest.mark.parametrize("case", ["scale_up", "scale_down", "offset", "mixed_columns", "small_next_to_big", "d32_offset"])
+@pytest.mark.parametrize("case", ["scale_up", "scale_down", "offset", "mixed_columns", "small_next_to_big", "d32_offset",
+                                  "tiny_magnitude"])
 def test_sweep_value_ranges(rls, orc, case):
     """The matrix path works on centred data scaled by a power of two into 16-bit range: magnitudes far from 1, means
     far from the spread, and columns that all but vanish next to the largest one must give the oracle's results
@@ -476,6 +477,10 @@ def test_sweep_value_ranges(rls, orc, case):
         d = 32
         centres = rng.standard_normal((12, d)) * 3.0
         X = centres[rng.integers(0, 12, size=N)] + rng.standard_normal((N, d)) * 0.4 + 1000.0
+    elif case == "tiny_magnitude":
+        # squared distances on both sides of 1e-30: below it the first, fp32 stage of the exact argmin hands over to
+        # fp64 (fp32 may have lost such a distance); integers times 2^-54, so the exact sums still hold every value
+        X = np.round(X * 16.0) * 2.0 ** -54
     X = X.astype(np.float32)
     res, ref = run_both(rls, orc, X, 1, 20, 6, seed=3)
     assert int(res.status.item()) == 0

@@ -47,3 +47,45 @@ def test_two_piece_products_stay_inside_the_bound(flush):
         worst = max(worst, float((np.abs(approx - exact) / bound).max()))
     assert worst <= 1.0
     assert worst > 0.01      # the model is exercised: the errors are not orders of magnitude below the bound
+
+
+def test_fp32_direct_form_first_stage_keeps_the_fp64_winner():
+    """The exact argmin of the Lloyd step settles most calls in fp32: direct-form distances (difference, square, running
+    sum with one rounding per multiply-add), then every centroid within 8 (d + 2) 2^-24 of the smallest stays a
+    candidate and fp64 decides only among several.  Model of that stage in numpy: the relative error of the fp32 form
+    against the exact distance is below (d + 2) 2^-24, and the fp64 winner (lowest index among equals) is always among
+    the candidates - also with near-ties planted a few fp32 units apart."""
+    rng = np.random.default_rng(41)
+    worst = 0.0
+    for trial in range(60):
+        d = int(rng.choice([8, 16, 32]))
+        k = int(rng.integers(2, 129))
+        scale = 2.0 ** rng.integers(-30, 30)
+        x = (rng.standard_normal(d) * scale).astype(np.float32)
+        c = (rng.standard_normal((k, d)) * scale).astype(np.float32)
+        if trial % 2 == 0:
+            # near-ties: mirror a centroid in x along one feature (the same distance up to rounding), nudge another copy
+            j, l = int(rng.integers(0, k - 1)), int(rng.integers(0, d))
+            c[j + 1] = c[j]
+            c[j + 1, l] = np.float32(2.0) * x[l] - c[j, l]
+            if k > 3:
+                c[(j + 2) % k] = np.nextafter(c[j], np.float32(np.inf))
+        # fp32 stage: sequential multiply-adds (the product and the sum are rounded once together: emulate in fp64, round)
+        acc = np.zeros(k, dtype=np.float32)
+        for l in range(d):
+            diff = (x[l] - c[:, l]).astype(np.float32)
+            acc = (diff.astype(np.float64) * diff.astype(np.float64) + acc.astype(np.float64)).astype(np.float32)
+        exact = ((x.astype(np.float64)[None, :] - c.astype(np.float64)) ** 2).sum(1)     # exact up to 2^-53 relative
+        rel = np.abs(acc.astype(np.float64) - exact) / np.maximum(exact, 1e-300)
+        worst = max(worst, float(rel.max() / ((d + 2) * 2.0 ** -24)))
+        # the oracle's decision: fp64 direct form with separately rounded multiply and add, lowest index among equals
+        d64 = np.zeros(k)
+        for l in range(d):
+            diff = x[l].astype(np.float64) - c[:, l].astype(np.float64)
+            d64 = d64 + diff * diff
+        winner = int(np.argmin(d64))
+        wmin = acc.min()
+        thr = np.float32(np.float64(wmin) * (8 * (d + 2)) * 2.0 ** -24 + np.float64(wmin))
+        assert acc[winner] <= thr
+    assert worst <= 1.0
+    assert worst > 0.02
