@@ -728,8 +728,8 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             for (int sl = 0; sl < NS; ++sl) dst[sl] = opA_s[(t * NS + sl) * 64 + lane];
         };
         load_a(a_even, 0);
-        if constexpr (NB == 1 && NK == 1) {
-            // One block per slab: the four MFMAs of a tile form one dependent chain, so the wave interleaves them in
+        if constexpr (NB == 1) {
+            // One block per slab: the four (d_pad = 32: seven) MFMAs of a tile form one dependent chain, so the wave interleaves them in
             // program order with the fold of the tile before - a quarter of the fold (one quad of rows) behind each MFMA -
             // and the two accumulators alternate by name.  The order is pinned: left to itself the compiler folds first
             // and then issues the chain into the same registers, and nothing of the wave overlaps.
@@ -762,19 +762,24 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
                 constexpr int kFold = decltype(fold)::value;
                 using Init = std::integral_constant<bool, kFold == 1>;
                 const floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1]), bx[0][0][0], zero, 0, 0, 0);        // l.h
+                // small cross terms first, then the leading one, then the bias slot: all in one fp32 accumulator; a quad of
+                // the other accumulator is folded behind the last MFMA of each of the four parts
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1 * NK]), bx[0][0][0], zero, 0, 0, 0);               // l.h
+                if constexpr (NK == 2) acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[1 * NK + 1]), bx[0][0][1], acc_new, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (kFold) fold_quad(acc_old, kidx_prev, 0, Init{});
                 __builtin_amdgcn_sched_barrier(0);
-                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][1][0], acc_new, 0, 0, 0);     // h.l
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[ks]), bx[0][1][ks], acc_new, 0, 0, 0);   // h.l
                 __builtin_amdgcn_sched_barrier(0);
                 if (kFold) fold_quad(acc_old, kidx_prev, 1, Init{});
                 __builtin_amdgcn_sched_barrier(0);
-                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[0]), bx[0][0][0], acc_new, 0, 0, 0);     // h.h
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) acc_new = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a_cur[ks]), bx[0][0][ks], acc_new, 0, 0, 0);   // h.h
                 __builtin_amdgcn_sched_barrier(0);
                 if (kFold) fold_quad(acc_old, kidx_prev, 2, Init{});
                 __builtin_amdgcn_sched_barrier(0);
-                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2]), bb[0], acc_new, 0, 0, 0);         // norms
+                acc_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a_cur[2 * NK]), bb[0], acc_new, 0, 0, 0);                 // norms
                 __builtin_amdgcn_sched_barrier(0);
                 if (kFold) fold_quad(acc_old, kidx_prev, 3, Init{});
                 __builtin_amdgcn_sched_barrier(0);
