@@ -13,11 +13,13 @@
 //            into two fp16 pieces (22 significant bits) and the three leading cross products are accumulated
 //            in fp32 (fp32-class accuracy; the 16-bit pipeline runs beside the vector ALU, the fp32 one does
 //            not); per point and run the two smallest packed (value, index) keys are kept.  When they are
-//            closer than the error bound of these distances the pair is decided again in fp64 with the direct
+//            closer than the error bound of these distances the pair is decided again with the direct
 //            form sum_l (x_l - c_l)^2 - the arithmetic that defines the assignment - by a scan of the whole
-//            run; labels never depend on fp32 or fp16 rounding
+//            run: in fp32 first, whose relative error bound leaves a single candidate almost always, then in
+//            fp64 among several; labels never depend on the rounding of the matrix-pipeline distances
 //   update   exact centroid sums, kept as running totals: only points whose label differs from the one
-//            of the previous round move their fixed-point row from the old cluster's int64 accumulators
+//            of the previous round (kept as one byte per point and run, the runs of a group side by side, so
+//            that a lane compares all its runs in one instruction) move their fixed-point row from the old cluster's int64 accumulators
 //            to the new one's (integer LDS atomics; integer adds commute and cancel exactly, so the totals
 //            equal a fresh sum in any order); per-chunk deltas go to global memory and lloyd_centroids_kernel
 //            adds them to the 128-bit totals, rounds once to fp64, divides by the count and rounds to fp32
