@@ -38,7 +38,6 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 namespace {
 
 constexpr int kThreads = 512;                // workgroup of the helper kernels (the step kernel: step_threads_of)
-constexpr int kWaves = kThreads / 64;
 constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding rows: never the minimum
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
 constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by the main accumulator
@@ -160,11 +159,6 @@ __device__ inline int xchg32(int v)
 }
 __device__ inline unsigned xchg32(unsigned v) { return (unsigned)xchg32((int)v); }
 __device__ inline float xchg32(float v) { return __int_as_float(xchg32(__float_as_int(v))); }
-__device__ inline double xchg32(double v)
-{
-    const int lo = xchg32(__double2loint(v)), hi = xchg32(__double2hiint(v));
-    return __hiloint2double(hi, lo);
-}
 
 // Minimum over the wave, in every lane, without a trip through LDS: lane exchanges inside rows of 16 by DPP (swap
 // neighbours, swap pairs, mirror halves of 8, mirror the row: after each step twice as many lanes agree), then
@@ -735,7 +729,7 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
             // program order with the fold of the tile before - a quarter of the fold (one quad of rows) behind each MFMA -
             // and the two accumulators alternate by name.  The order is pinned: left to itself the compiler folds first
             // and then issues the chain into the same registers, and nothing of the wave overlaps.
-            floatx16 acc_a, acc_b;
+            floatx16 acc_a, acc_b = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};     // (acc_b: never read before the second tile writes it)
             int kidx_prev[16];
             // `init`: the first tile of a slab - the first two keys of a run start its pair of smallest keys outright
             // (no sentinel values to set up and compare against)
