@@ -45,7 +45,11 @@ def test_gbt_score_tiny(rls, orc):
                                      (2049, 5, 7, 12), (4096, 16, 70, 6),
                                      # many shallow trees: more leaves per byte of forest than deep trees have
                                      (600, 32, 1200, 3), (700, 20, 4500, 1), (513, 32, 2300, 2), (1100, 16, 9000, 1),
-                                     (300, 24, 3, 12), (900, 8, 300, 4)])
+                                     (300, 24, 3, 12), (900, 8, 300, 4),
+                                     # tiles of 1024 and of 896 configurations, chunks of 4, 2 and 1 trees, chunks moved
+                                     # four entries at a time and (a last chunk of 3 trees, 30 features) one at a time
+                                     (2000, 32, 23, 10), (1800, 32, 24, 10), (1100, 32, 13, 9), (950, 32, 5, 11),
+                                     (900, 32, 3, 12), (1030, 16, 7, 11), (1900, 30, 10, 10), (2100, 32, 64, 8)])
 def test_gbt_score_shapes(rls, orc, N, d, T, D):
     rng = np.random.default_rng(N + d)
     X = rng.standard_normal((N, d)).astype(np.float32)
@@ -70,6 +74,25 @@ def test_gbt_score_feature_index_out_of_range_reads_the_border_column(rls, orc):
     inside = synth.Forest(f.n_trees, f.depth, f.n_features, f.base, np.clip(bad.feat, 0, 11), f.thr, f.leaf)
     got = rls.gbt_score(rls.DeviceForest.from_host(bad), dev(X)).cpu().numpy()
     np.testing.assert_array_equal(got, orc.gbt_score(inside, X)[0])
+
+
+def test_gbt_score_forest_arrays_not_16_byte_aligned(rls, orc):
+    """Forest arrays that start 4 bytes past a 16-byte boundary (views into larger buffers): same scores."""
+    rng = np.random.default_rng(23)
+    X = rng.standard_normal((1500, 32)).astype(np.float32)
+    f = synth.random_forest(X, 16, 10, 0, rng)
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.as_tensor(a).dtype, device="cuda")
+        buf[1:] = torch.as_tensor(a).reshape(-1).cuda()
+        v = buf[1:].view(a.shape)
+        assert v.data_ptr() % 16 == 4
+        return v
+
+    F = rls.DeviceForest(f.n_trees, f.depth, f.n_features, f.base, shifted(f.feat), shifted(f.thr), shifted(f.leaf))
+    assert F.feat.data_ptr() % 16 == 4 and F.thr.data_ptr() % 16 == 4 and F.leaf.data_ptr() % 16 == 4
+    got = rls.gbt_score(F, dev(X)).cpu().numpy()
+    np.testing.assert_array_equal(got, orc.gbt_score(f, X)[0])
 
 
 def test_gbt_score_mid_subset(rls, orc):
