@@ -38,6 +38,14 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 namespace {
 
 constexpr int kThreads = 512;                // workgroup of the helper kernels (the step kernel: step_threads_of)
+constexpr int kPartRows = 8;                 // centroids of a run that one workgroup of the centroid kernel renews
+constexpr int kMaxParts = RLS_MAX_K / kPartRows;
+// parts of the runs k' = 1 .. k together: the sum of ceil(k' / kPartRows)
+__host__ __device__ inline int parts_upto(int k)
+{
+    const int q = k / kPartRows;
+    return kPartRows * q * (q + 1) / 2 + (k - kPartRows * q) * (q + 1);
+}
 constexpr float kPadNorm = 1.0e30f;           // squared norm given to padding rows: never the minimum
 constexpr int kBigKey = 0x7f000000;           // larger than any key of a finite distance below 1.7e38
 constexpr int kGridBits = 44;                 // bits of |x * 2^shift| kept by the main accumulator
@@ -1276,7 +1284,16 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
             }
         }
         if (tid == 0) *next_slab = WV;
-        if (tid < 8) cnmax_s[tid] = tid < g.n_runs ? reinterpret_cast<const float *>(wsb + a.off_cnmax)[g.run0 + tid] : 0.0f;
+        if (tid < 8) {
+            // the largest squared norm of the run's centroids: the centroid kernel leaves one maximum per part of the run
+            float m = 0.0f;
+            if (tid < g.n_runs) {
+                const float *parts = reinterpret_cast<const float *>(wsb + a.off_cnmax) + (g.run0 + tid) * kMaxParts;
+                const int n_parts = (plan.k_min + g.run0 + tid + kPartRows - 1) / kPartRows;
+                for (int p = 0; p < n_parts; ++p) m = fmaxf(m, parts[p]);
+            }
+            cnmax_s[tid] = m;
+        }
         if (!FINAL) {
             for (int e = tid; e < copies * real_rows * (DP + 1); e += TH) sums[e] = 0ull;
             for (int e = tid; e < copies * real_rows; e += TH) cnts[e] = 0;
@@ -1660,18 +1677,26 @@ struct CentroidArgs {
     int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_losum, off_tot, off_totcnt;
 };
 
-// One workgroup per run: new centroids (from the seeding rows, or from the running totals after adding
-// this round's per-chunk deltas), then the centred, -2-scaled MFMA operand rows and their squared norms.
+// One workgroup per run and part of kPartRows of its centroids: new centroids (from the seeding rows, or from the
+// running totals after adding this round's per-chunk deltas), then the centred, -2-scaled MFMA operand rows and their
+// squared norms.  (One workgroup per run left the large runs to the memory bandwidth of a single compute unit.)
 template <int DP, bool INIT>
 __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan plan, CentroidArgs a)
 {
-    __shared__ float cs[RLS_MAX_K * DP];     // centred centroids of this run
-    __shared__ float wmax[kThreads / 64];
+    static_assert(kPartRows * DP <= kThreads, "one thread per (centroid, feature) element of a part");
+    __shared__ float cs[kPartRows * DP];     // centred centroids of this part
     __shared__ long long part_hi[INIT ? 1 : kThreads], part_cnt[INIT ? 1 : kThreads];
     __shared__ unsigned long long part_lo[INIT ? 1 : kThreads];
-    const int b = blockIdx.y, run = blockIdx.x, tid = threadIdx.x;
+    const int b = blockIdx.y, tid = threadIdx.x;
     if (a.status[b] != 0) return;
+    // blockIdx.x counts the parts of all runs in run order: the run is the last one that starts at or before it
+    const int parts0 = parts_upto(plan.k_min - 1);
+    int run = 0;
+    for (int step = 64; step >= 1; step >>= 1)
+        if (run + step < plan.n_runs && parts_upto(plan.k_min + run + step - 1) - parts0 <= (int)blockIdx.x) run += step;
     const int d = a.d, k = plan.k_min + run;
+    const int part = (int)blockIdx.x - (parts_upto(k - 1) - parts0);
+    const int j0 = part * kPartRows, rows = min(kPartRows, k - j0);
     const int row0 = rows_before(plan.k_min, run);
     int gi = 0;
     while (gi + 1 < plan.n_groups && plan.g[gi + 1].run0 <= run) ++gi;
@@ -1687,13 +1712,13 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
     unsigned short *opA = reinterpret_cast<unsigned short *>(wsb + a.off_opA + (int64_t)g.tile0 * tile_bytes_of(DP));
     constexpr int NK = ksteps_of(DP), NS = tile_slots_of(DP);
 
-    // A run with few (centroid, feature) elements splits the chunks over `nsl` thread slices per element, so that
-    // the per-chunk deltas are not read one after the other by a handful of threads; integer sums, any order.
-    const int E = k * DP;
-    const int nsl = (!INIT && E < kThreads) ? kThreads / E : 1;
-    if (nsl > 1) {
+    // The chunks are split over `nsl` thread slices per (centroid, feature) element, so that the per-chunk deltas are
+    // not read one after the other by a handful of threads; integer sums, any order.
+    const int E = rows * DP;
+    const int nsl = INIT ? 1 : kThreads / E;
+    if (!INIT) {
         const int e = tid % E, sl = tid / E;
-        const int j = e / DP, l = e % DP;
+        const int j = j0 + e / DP, l = e % DP;
         long long hi = 0, cnt = 0;
         unsigned long long lo = 0;
         if (sl < nsl && l < d) {
@@ -1706,8 +1731,9 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         __syncthreads();
     }
 
-    for (int e = tid; e < k * DP; e += kThreads) {
-        const int j = e / DP, l = e % DP;
+    if (tid < E) {
+        const int e = tid;
+        const int jj = e / DP, j = j0 + jj, l = e % DP;
         float cp = 0.0f;
         if (l < d) {
             float c;
@@ -1716,23 +1742,16 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
                 c = a.X[(int64_t)b * a.x_bs + src * a.ldx + l];
                 Cb[(int64_t)(row0 + j) * d + l] = c;
             } else {
-                const long long *psum = reinterpret_cast<const long long *>(wsb + a.off_psum);
-                const int *pcnt = reinterpret_cast<const int *>(wsb + a.off_pcnt);
                 long long *tot = reinterpret_cast<long long *>(wsb + a.off_tot) + ((int64_t)(row0 + j) * d + l) * 2;
                 long long *totcnt = reinterpret_cast<long long *>(wsb + a.off_totcnt) + (int64_t)(row0 + j) * d + l;
                 long long hi = tot[0];
                 unsigned long long lo = (unsigned long long)tot[1];
                 long long cnt = *totcnt;
-                if (nsl > 1) {
-                    for (int sl = 0; sl < nsl; ++sl) {
-                        const unsigned long long nlo = lo + part_lo[sl * E + e];
-                        hi += part_hi[sl * E + e] + (nlo < lo ? 1 : 0);
-                        lo = nlo;
-                        cnt += part_cnt[sl * E + e];
-                    }
-                } else {
-                    sum_chunks(psum + (int64_t)(row0 + j) * d + l, pcnt + row0 + j, (int64_t)plan.total_rows * d,
-                               plan.total_rows, 0, plan.n_chunks, hi, lo, cnt);
+                for (int sl = 0; sl < nsl; ++sl) {
+                    const unsigned long long nlo = lo + part_lo[sl * E + e];
+                    hi += part_hi[sl * E + e] + (nlo < lo ? 1 : 0);
+                    lo = nlo;
+                    cnt += part_cnt[sl * E + e];
                 }
                 tot[0] = hi;
                 tot[1] = (long long)lo;
@@ -1757,7 +1776,7 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
             }
             cp = fmaf(c, scale, colmean[l]);     // (c - mean) * scale, one rounding, as for the points
         }
-        cs[j * DP + l] = cp;
+        cs[jj * DP + l] = cp;
         // operand position of (centroid j, feature l)
         const int qd = j >> 2, i = j & 3;
         const int t = qd / g.S, slot = rl * g.S + qd % g.S;
@@ -1771,9 +1790,10 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
     }
     __syncthreads();
     float mx = 0.0f;
-    for (int j = tid; j < k; j += kThreads) {
+    if (tid < rows) {
+        const int j = j0 + tid;
         float nrm = 0.0f;
-        for (int l = 0; l < DP; ++l) nrm = fmaf(cs[j * DP + l], cs[j * DP + l], nrm);
+        for (int l = 0; l < DP; ++l) nrm = fmaf(cs[tid * DP + l], cs[tid * DP + l], nrm);
         const int qd = j >> 2, i = j & 3;
         const int t = qd / g.S, slot = rl * g.S + qd % g.S;
         // bias slot, lower half-wave lane of this row: pieces of the squared norm
@@ -1782,15 +1802,12 @@ __global__ void __launch_bounds__(kThreads) lloyd_centroids_kernel(SweepPlan pla
         const int m = 8 * (slot & 3) + 4 * (slot >> 2) + i;
         unsigned short *bias = opA + ((int64_t)(t * NS + 2 * NK) * 64 + m) * 8;
         bias[0] = (unsigned short)ph; bias[1] = (unsigned short)pm; bias[2] = (unsigned short)pl;
-        mx = fmaxf(mx, nrm);
+        mx = nrm;
     }
-    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    if ((tid & 63) == 0) wmax[tid >> 6] = mx;
-    __syncthreads();
-    if (tid == 0) {
-        float m = wmax[0];
-        for (int w = 1; w < kThreads / 64; ++w) m = fmaxf(m, wmax[w]);
-        reinterpret_cast<float *>(wsb + a.off_cnmax)[run] = m;
+    // rows <= 64: the first wave holds them all; the run's maximum is taken over its parts by the reader
+    if (tid < 64) {
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        if (tid == 0) reinterpret_cast<float *>(wsb + a.off_cnmax)[run * kMaxParts + part] = mx;
     }
 }
 
@@ -1869,7 +1886,8 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     ca.status = a.status; ca.ws = a.ws; ca.ws_bs = L.per_batch;
     ca.off_colinfo = L.colinfo; ca.off_opA = L.opA; ca.off_cnmax = L.cnmax;
     ca.off_psum = L.psum; ca.off_pcnt = L.pcnt; ca.off_losum = L.losum; ca.off_tot = L.tot; ca.off_totcnt = L.totcnt;
-    hipLaunchKernelGGL((lloyd_centroids_kernel<DP, true>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
+    const dim3 centroid_grid(parts_upto(plan.k_min + plan.n_runs - 1) - parts_upto(plan.k_min - 1), batch);
+    hipLaunchKernelGGL((lloyd_centroids_kernel<DP, true>), centroid_grid, dim3(kThreads), 0, s, plan, ca);
 
     StepArgs sa;
     sa.X = a.X; sa.N = a.N; sa.d = a.d; sa.ldx = a.ldx; sa.x_bs = a.x_batch_stride;
@@ -1904,7 +1922,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
             else hipLaunchKernelGGL((lloyd_step_kernel<DP, false, false, true>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
             if (prof) { hipError_t e = profile_mark(s, false); if (e != hipSuccess) return e; }
         }
-        hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), dim3(plan.n_runs, batch), dim3(kThreads), 0, s, plan, ca);
+        hipLaunchKernelGGL((lloyd_centroids_kernel<DP, false>), centroid_grid, dim3(kThreads), 0, s, plan, ca);
     }
     hipLaunchKernelGGL((lloyd_step_kernel<DP, true, false, false>), grid, dim3(step_threads_of(DP)), lds, s, plan, sa);
     hipLaunchKernelGGL(lloyd_loss_kernel, dim3(batch), dim3(128), 0, s, plan.n_runs, plan.n_chunks, a.status, a.ws, L.per_batch,
@@ -2032,7 +2050,7 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->mind = take(N * 8);
     L->bsum = take((int64_t)L->seed_blocks * 8);
     L->opA = take((int64_t)plan.total_tiles * tile_bytes_of(plan.dp));
-    L->cnmax = take((int64_t)plan.n_runs * 4);
+    L->cnmax = take((int64_t)plan.n_runs * kMaxParts * 4);
     L->psum = take((int64_t)plan.n_chunks * plan.total_rows * d * 8);
     L->pcnt = take((int64_t)plan.n_chunks * plan.total_rows * 4);
     L->pj = take((int64_t)plan.n_chunks * plan.n_runs * 8);

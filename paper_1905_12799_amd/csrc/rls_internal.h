@@ -82,7 +82,7 @@ struct SweepLayout {
     int64_t mind;           // fp64 [N] squared distance to the nearest chosen centre
     int64_t bsum;           // fp64 [seed blocks] block sums of mind
     int64_t opA;            // per 32-row tile: fp16 pieces of the centred, -2-scaled centroids and the bf16 bias slot, in MFMA operand order
-    int64_t cnmax;          // fp32 [n_runs] per-run maximum of cn
+    int64_t cnmax;          // fp32 [n_runs][parts of a run] maximum of cn over the centroids of a part
     int64_t psum;           // int64 [n_chunks][total_rows][d] per-chunk changes of the fixed-point sums
     int64_t pcnt;           // int32 [n_chunks][total_rows] per-chunk changes of the member counts
     int64_t pj;             // fp64 [n_chunks][n_runs] partial losses
