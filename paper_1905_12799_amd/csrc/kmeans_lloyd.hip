@@ -2049,6 +2049,8 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->chain = take((int64_t)k_max * 8);
     L->mind = take(N * 8);
     L->bsum = take((int64_t)L->seed_blocks * 8);
+    L->near = take(N);
+    L->seedthr = take((int64_t)k_max * 8);
     L->opA = take((int64_t)plan.total_tiles * tile_bytes_of(plan.dp));
     L->cnmax = take((int64_t)plan.n_runs * kMaxParts * 4);
     L->psum = take((int64_t)plan.n_chunks * plan.total_rows * d * 8);

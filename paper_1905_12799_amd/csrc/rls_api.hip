@@ -66,7 +66,7 @@ using namespace rls;
 
 extern "C" {
 
-int32_t rls_version(void) { return 124; }
+int32_t rls_version(void) { return 125; }
 
 const char *rls_error_string(int32_t code)
 {
@@ -160,9 +160,7 @@ int32_t rls_kmeanspp_chain(const float *X_dev, int64_t N, int32_t d, int64_t ldx
     sweep_layout(plan, N, d, k_max, 1, &L);
     if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < L.total) return RLS_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace_dev);
-    RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_max, &seed, init_idx_dev, k_max,
-                                  reinterpret_cast<double *>(ws + L.mind), 0, reinterpret_cast<double *>(ws + L.bsum), 0,
-                                  L.seed_blocks, (hipStream_t)stream));
+    RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_max, &seed, init_idx_dev, k_max, ws, L, (hipStream_t)stream));
     return RLS_OK;
 }
 
@@ -194,9 +192,7 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
     int64_t init_bs = k_max;
     if (!init) {
         int64_t *chain = reinterpret_cast<int64_t *>(ws + L.chain);
-        RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, x_batch_stride, batch, k_max, seeds, chain, L.per_batch / 8,
-                                      reinterpret_cast<double *>(ws + L.mind), L.per_batch / 8,
-                                      reinterpret_cast<double *>(ws + L.bsum), L.per_batch / 8, L.seed_blocks, s));
+        RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, x_batch_stride, batch, k_max, seeds, chain, L.per_batch / 8, ws, L, s));
         init = chain;
         init_bs = L.per_batch / 8;
     }
@@ -279,9 +275,7 @@ int32_t rls_kmeans_sweep_until_knee(const float *X_dev, int64_t N, int32_t d, in
         if (!init) {
             // the chain grows with the waves: centres chain_done .. k_hi-1 are drawn now, from the distance state of the earlier ones
             int64_t *chain = reinterpret_cast<int64_t *>(ws + L.chain);
-            RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_hi, &seed, chain, k_max,
-                                          reinterpret_cast<double *>(ws + L.mind), 0, reinterpret_cast<double *>(ws + L.bsum), 0,
-                                          L.seed_blocks, s, chain_done));
+            RLS_HIP_TRY(launch_seed_chain(X_dev, N, d, ldx, 0, 1, k_hi, &seed, chain, k_max, ws, L, s, chain_done));
             chain_done = k_hi;
             init = chain;
         }

@@ -81,6 +81,8 @@ struct SweepLayout {
     int64_t chain;          // int64 [k_max] seeding chain
     int64_t mind;           // fp64 [N] squared distance to the nearest chosen centre
     int64_t bsum;           // fp64 [seed blocks] block sums of mind
+    int64_t near;           // uint8 [N] chain position of the nearest chosen centre
+    int64_t seedthr;        // fp64 [k_max] per chosen centre: the bound below which a point's distance cannot improve
     int64_t opA;            // per 32-row tile: fp16 pieces of the centred, -2-scaled centroids and the bf16 bias slot, in MFMA operand order
     int64_t cnmax;          // fp32 [n_runs][parts of a run] maximum of cn over the centroids of a part
     int64_t psum;           // int64 [n_chunks][total_rows][d] per-chunk changes of the fixed-point sums
@@ -132,8 +134,7 @@ hipError_t launch_apply_actions(const int32_t *cfg, const signed char *action, i
 
 hipError_t launch_seed_chain(const float *X, int64_t N, int32_t d, int64_t ldx, int64_t x_batch_stride, int32_t batch,
                              int32_t k_max, const uint64_t *seeds_host, int64_t *chain, int64_t chain_batch_stride,
-                             double *mind, int64_t mind_batch_stride, double *bsum, int64_t bsum_batch_stride,
-                             int32_t seed_blocks, hipStream_t s, int32_t j_begin = 0);
+                             char *ws, const SweepLayout &L, hipStream_t s, int32_t j_begin = 0);
 
 struct SweepArgs {
     const float *X;

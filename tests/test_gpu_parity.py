@@ -266,6 +266,25 @@ def test_seeding_chain(rls, orc, name, N, k_max):
         np.testing.assert_array_equal(got, orc.kmeanspp_chain(p.X, k_max, seed))
 
 
+@pytest.mark.parametrize("N,d,span,stride", [(5000, 2, 6, None), (30011, 4, 3, None), (9000, 8, 2, 12), (7001, 5, 4, None),
+                                             (20000, 16, 1, None), (3000, 32, 2, 40)])
+def test_seeding_chain_lattice_points(rls, orc, N, d, span, stride):
+    """Integer lattices: many duplicates, and many points exactly half way between two centres, where the bound
+    that lets the update skip a row (D_i against a quarter of the squared distance between centres) is met with
+    equality; rows that are not 16-byte multiples or are strided take the element-wise read path."""
+    rng = np.random.default_rng(N + d)
+    X = rng.integers(0, span + 1, size=(N, d)).astype(np.float32)
+    Xd = dev(X)
+    if stride is not None:
+        wide = torch.zeros((N, stride), dtype=torch.float32, device="cuda")
+        wide[:, :d] = Xd
+        Xd = wide[:, :d]
+    k_max = min(64, (span + 1) ** d + 3)          # more centres than distinct points where the lattice is small
+    for seed in (1, 2):
+        got = rls.kmeanspp_chain(Xd, k_max, seed).cpu().numpy()
+        np.testing.assert_array_equal(got, orc.kmeanspp_chain(X, k_max, seed))
+
+
 def test_seeding_all_points_equal(rls, orc):
     X = np.full((300, 8), 3.0, dtype=np.float32)
     got = rls.kmeanspp_chain(dev(X), 5, 11).cpu().numpy()

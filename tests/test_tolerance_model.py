@@ -89,3 +89,41 @@ def test_fp32_direct_form_first_stage_keeps_the_fp64_winner():
         assert acc[winner] <= thr
     assert worst <= 1.0
     assert worst > 0.02
+
+
+def test_seeding_skip_rule_never_skips_a_point_that_would_improve():
+    """The seeding update leaves a point's row unread when D_i <= (1 - 2^-30) / 4 * |c_a - c_new|^2, a being the
+    point's nearest earlier centre (triangle inequality).  Model of the rule in numpy, in the kernel's arithmetic
+    (fp64 direct form on fp32 rows): no skipped point may have a strictly smaller distance to the new centre -
+    on lattice data, where D_i = |c_a - c_new|^2 / 4 holds exactly for many points, on duplicates and on
+    continuous data of very different scales."""
+    rng = np.random.default_rng(77)
+    cases = []
+    for dims, span in ((2, 6), (3, 4), (8, 3), (16, 2)):
+        cases.append(rng.integers(0, span + 1, size=(4000, dims)).astype(np.float32))
+    cases.append((rng.standard_normal((4000, 16)) * 1e-6).astype(np.float32))
+    cases.append((rng.standard_normal((4000, 32)) * 3e5 + 1e6).astype(np.float32))
+    line = np.zeros((4001, 4), dtype=np.float32)
+    line[:, 0] = np.arange(4001) * 0.5                         # midpoints between centres are data points
+    cases.append(line)
+    skipped_total = 0
+    for X32 in cases:
+        X = X32.astype(np.float64)
+        n = X.shape[0]
+        chain = [int(rng.integers(n))]
+        D = ((X - X[chain[0]]) ** 2).sum(1)
+        near = np.zeros(n, dtype=np.int64)
+        for j in range(1, 24):
+            pick = int(rng.integers(n))
+            c = X[pick]
+            dcc = ((X[chain] - c) ** 2).sum(1)
+            thr = dcc * (0.25 * (1.0 - 2.0 ** -30))
+            skip = D <= thr[near]
+            dn = ((X - c) ** 2).sum(1)
+            assert not np.any(skip & (dn < D))
+            skipped_total += int(skip.sum())
+            better = dn < D
+            D = np.where(better, dn, D)
+            near = np.where(better, j, near)
+            chain.append(pick)
+    assert skipped_total > 100000        # the rule does fire on these inputs
