@@ -282,3 +282,59 @@ def test_batched_full(rls, orc):
     for b in (0, 63):
         rows = np.random.default_rng(b).choice(w.N, size=2048, replace=False)
         np.testing.assert_array_equal(scores[b, rows], orc.gbt_score(probs[b].forest, probs[b].X[rows])[0])
+
+
+@pytest.mark.timeout(900)
+def test_maximum_number_of_points(rls, orc):
+    """N = RLS_MAX_N = 2^26 rows of 32 features (8 GiB of rows: element offsets reach 2^31, byte offsets 2^33), every
+    kernel that walks the rows: complete oracle runs of Lloyd (one k that takes the prepared-copy path from the second
+    round on, two small k side by side), the head of the seeding chain, sampled tree scores including the last
+    row, histograms and modes over all rows.  The rows are 16 copies of a 4M-row draw of the 8M workload's
+    generator, copy c shifted by c / 4 in the last column so that no two copies coincide."""
+    w = synth.WORKLOADS["large"]
+    M, copies = 1 << 22, 16
+    N = M * copies
+    assert N == 1 << 26
+    progress("max N: generating 2^26 x 32")
+    p = synth.make_problem(w, N=M)
+    X = np.empty((N, w.d), dtype=np.float32)
+    for c in range(copies):
+        X[c * M:(c + 1) * M] = p.X
+        X[c * M:(c + 1) * M, w.d - 1] += np.float32(0.25 * c)
+    Xd = torch.from_numpy(X).cuda()
+    # tree scores
+    progress("max N: tree scores")
+    scores = rls.gbt_score(rls.DeviceForest.from_host(p.forest), Xd)
+    rows = np.unique(np.concatenate([[0, M - 1, M, N - 2, N - 1], np.random.default_rng(26).choice(N, size=4096, replace=False)]))
+    got = scores[torch.as_tensor(rows).cuda()].cpu().numpy()
+    np.testing.assert_array_equal(got, orc.gbt_score(p.forest, X[rows])[0])
+    del scores
+    # seeding chain: the first draws (the oracle's chain is sequential)
+    progress("max N: seeding chain")
+    chain = orc.kmeanspp_chain(X, 3, w.seed)
+    np.testing.assert_array_equal(rls.kmeanspp_chain(Xd, 3, w.seed).cpu().numpy(), chain)
+    # one k above a tile of centroids: two rounds, the second on the prepared copy; initial centres spread over all
+    # rows, the last row among them
+    k = 33
+    init = np.linspace(0, N - 1, k).astype(np.int64)
+    assert init[-1] == N - 1
+    progress(f"max N: GPU sweep k={k}, 2 rounds")
+    res = rls.kmeans_sweep(Xd, k, k, 2, init_idx=torch.as_tensor(init).cuda())
+    torch.cuda.synchronize()
+    assert check_run_against_oracle(orc, X, init, k, 2, res.labels[0].cpu().numpy(), res.centroids_of(k).cpu().numpy(),
+                                    float(res.inertia[0])) == 0
+    del res
+    # two small k side by side from the seeded chain, one round
+    progress("max N: GPU sweep k=2..3, 1 round")
+    res = rls.kmeans_sweep(Xd, 2, 3, 1, seed=w.seed)
+    torch.cuda.synchronize()
+    for kk in (2, 3):
+        assert check_run_against_oracle(orc, X, chain, kk, 1, res.labels[kk - 2].cpu().numpy(), res.centroids_of(kk).cpu().numpy(),
+                                        float(res.inertia[kk - 2])) == 0
+    del res
+    progress("max N: modes")
+    mode, hist = rls.knob_modes(Xd, rls.DeviceDomains(p.dom_offsets, p.dom_values))
+    mode_o, hist_o = orc.knob_modes(X, p.dom_offsets, p.dom_values)
+    np.testing.assert_array_equal(hist.cpu().numpy().astype(np.int64), hist_o)
+    np.testing.assert_array_equal(mode.cpu().numpy(), mode_o)
+    progress("max N: done")
