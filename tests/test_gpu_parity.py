@@ -464,6 +464,22 @@ def test_sweep_batched(rls, orc):
         compare_sweep(orc, p.X, one, ref, 1, 32)
 
 
+@pytest.mark.parametrize("batch,N,d,k_max,iters", [(130, 700, 8, 6, 3), (1024, 300, 5, 4, 2)])
+def test_sweep_many_spaces(rls, orc, batch, N, d, k_max, iters):
+    """More spaces than one launch of the seeding kernels takes (they go 64 at a time), up to the largest batch the
+    library accepts; every space against the oracle, the snapped centroids of one k as well."""
+    rng = np.random.default_rng(batch)
+    X = (rng.integers(0, 12, size=(batch, N, d)) + rng.standard_normal((batch, N, d)) * 0.25).astype(np.float32)
+    seeds = [1000 + 7 * b for b in range(batch)]
+    res = rls.kmeans_sweep_batched(dev(X), 1, k_max, iters, seeds=seeds)
+    torch.cuda.synchronize()
+    lab, cen, J, st = res.labels.cpu(), res.centroids.cpu(), res.inertia.cpu(), res.status.cpu()
+    for b in range(batch):
+        ref = orc.kmeans_sweep(X[b], 1, k_max, iters, seed=seeds[b])
+        one = rls.SweepResult(1, k_max, d, lab[b], cen[b], J[b], None, st[b:b + 1])
+        compare_sweep(orc, X[b], one, ref, 1, k_max)
+
+
 def test_sweep_strided_unaligned_rows_and_small_d(rls, orc):
     # rows 11 floats apart and starting 4 bytes off a 16-byte boundary: the scalar load paths
     rng = np.random.default_rng(21)
