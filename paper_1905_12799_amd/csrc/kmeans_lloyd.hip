@@ -1398,20 +1398,30 @@ __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restr
     const int64_t r0 = (int64_t)blockIdx.x * per, r1 = min(N, r0 + per);
     ColPart c = {0.0, 1 << 20, -(1 << 20), 0, 0, INFINITY, -INFINITY, {0, 0}};
     if (l < d) {
-        for (int64_t r = r0 + pg; r < r1; r += ppp) {
-            const float x = Xb[r * ldx + l];
-            const unsigned u = __float_as_uint(x);
-            int e = (int)((u >> 23) & 0xffu);
-            unsigned m = u & 0x7fffffu;
-            if (e == 255) { c.bad = 1; continue; }
-            c.sum = __dadd_rn(c.sum, (double)x);
-            c.vmin = fminf(c.vmin, x);
-            c.vmax = fmaxf(c.vmax, x);
-            if (e == 0) { if (m == 0) continue; e = 1; } else m |= 0x800000u;
-            const int lsb = e - 150 + (__ffs((int)m) - 1);
-            const int msb = e - 150 + (31 - __clz((int)m));
-            c.min_lsb = min(c.min_lsb, lsb);
-            c.max_msb = max(c.max_msb, msb);
+        // eight rows of this thread's column in flight at a time (the walk is bound by their latency); the values
+        // are taken in row order, so the sum does not depend on the depth
+        constexpr int U = 8;
+        for (int64_t rb = r0 + pg; rb < r1; rb += (int64_t)U * ppp) {
+            float xs[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) xs[u] = Xb[min(rb + (int64_t)u * ppp, r1 - 1) * ldx + l];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (rb + (int64_t)u * ppp >= r1) continue;
+                const float x = xs[u];
+                const unsigned bits = __float_as_uint(x);
+                int e = (int)((bits >> 23) & 0xffu);
+                unsigned m = bits & 0x7fffffu;
+                if (e == 255) { c.bad = 1; continue; }
+                c.sum = __dadd_rn(c.sum, (double)x);
+                c.vmin = fminf(c.vmin, x);
+                c.vmax = fmaxf(c.vmax, x);
+                if (e == 0) { if (m == 0) continue; e = 1; } else m |= 0x800000u;
+                const int lsb = e - 150 + (__ffs((int)m) - 1);
+                const int msb = e - 150 + (31 - __clz((int)m));
+                c.min_lsb = min(c.min_lsb, lsb);
+                c.max_msb = max(c.max_msb, msb);
+            }
         }
     }
     sh[tid] = c;
@@ -1431,27 +1441,26 @@ __global__ void __launch_bounds__(kThreads) colstats_kernel(const float *__restr
     }
 }
 
-__global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, int64_t ws_bs, int64_t off_part,
-                                      int64_t off_colinfo, int32_t *status)
+__global__ void __launch_bounds__(256) colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, int64_t ws_bs, int64_t off_part,
+                                                            int64_t off_colinfo, int32_t *status)
 {
+    // 256 threads: eight walk the partial results of one column, every eighth block each, eight loads in flight (the
+    // walk is bound by their latency); the eight are then combined in a fixed order, so the mean is the same in every run
+    constexpr int G = 8, U = 8;
     __shared__ int flags;
-    const int b = blockIdx.x, l = threadIdx.x;   // 32 threads
-    if (l == 0) flags = 0;
-    __syncthreads();
+    __shared__ ColPart comb[G][32];
+    const int b = blockIdx.x, l = threadIdx.x & 31, g = threadIdx.x >> 5;
+    if (threadIdx.x == 0) flags = 0;
     const ColPart *part = reinterpret_cast<const ColPart *>(ws + (int64_t)b * ws_bs + off_part);
-    float mean = 0.0f;
-    int shift = 0, wide = 0, msb = -(1 << 20);
+    ColPart t = {0.0, 1 << 20, -(1 << 20), 0, 0, INFINITY, -INFINITY, {0, 0}};
     if (l < d) {
-        ColPart t = part[l];
-        // four partial results in flight at a time (the walk is bound by their latency); the sums keep the block order
-        constexpr int U = 4;
-        for (int g0 = 1; g0 < n_blocks; g0 += U) {
+        for (int g0 = g; g0 < n_blocks; g0 += G * U) {
             ColPart o[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) o[u] = part[min(g0 + u, n_blocks - 1) * 32 + l];
+            for (int u = 0; u < U; ++u) o[u] = part[min(g0 + u * G, n_blocks - 1) * 32 + l];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (g0 + u >= n_blocks) continue;
+                if (g0 + u * G >= n_blocks) continue;
                 t.sum = __dadd_rn(t.sum, o[u].sum);
                 t.min_lsb = min(t.min_lsb, o[u].min_lsb);
                 t.max_msb = max(t.max_msb, o[u].max_msb);
@@ -1460,42 +1469,64 @@ __global__ void colstats_final_kernel(int64_t N, int d, int n_blocks, char *ws, 
                 t.vmax = fmaxf(t.vmax, o[u].vmax);
             }
         }
-        if (t.bad) atomicOr(&flags, RLS_STATUS_NONFINITE);
-        else {
-            mean = (float)(t.sum / (double)N);
-            // largest distance of a value (or of a centroid, which lies between the extremes) from the mean; the
-            // exponent of the next power of two above it, with the rounding of the two differences allowed for
-            const float reach = fmaxf(t.vmax - mean, mean - t.vmin) * 1.000001f;
-            if (reach > 0.0f) msb = ilogbf(reach);
-            if (t.max_msb >= t.min_lsb) {
-                // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk moves
-                // at most 2^17 rows in and out of a cluster within 63 bits. Bits below the grid (wide columns) go to
-                // the low accumulator, which keeps kLowBits more; anything finer cannot be summed exactly.
-                int grid = t.max_msb - (kGridBits - 1);
-                if (grid < t.min_lsb) grid = t.min_lsb;
-                shift = -grid;
-                if (t.min_lsb < grid) wide = 1;
-                if (t.min_lsb < grid - kLowBits) atomicOr(&flags, RLS_STATUS_RANGE);
+    }
+    comb[g][l] = t;
+    __syncthreads();
+    float mean = 0.0f;
+    int shift = 0, wide = 0, msb = -(1 << 20);
+    if (g == 0) {
+        if (l < d) {
+            for (int q = 1; q < G; ++q) {
+                const ColPart o = comb[q][l];
+                t.sum = __dadd_rn(t.sum, o.sum);
+                t.min_lsb = min(t.min_lsb, o.min_lsb);
+                t.max_msb = max(t.max_msb, o.max_msb);
+                t.bad |= o.bad;
+                t.vmin = fminf(t.vmin, o.vmin);
+                t.vmax = fmaxf(t.vmax, o.vmax);
+            }
+            if (t.bad) atomicOr(&flags, RLS_STATUS_NONFINITE);
+            else {
+                mean = (float)(t.sum / (double)N);
+                // largest distance of a value (or of a centroid, which lies between the extremes) from the mean; the
+                // exponent of the next power of two above it, with the rounding of the two differences allowed for
+                const float reach = fmaxf(t.vmax - mean, mean - t.vmin) * 1.000001f;
+                if (reach > 0.0f) msb = ilogbf(reach);
+                if (t.max_msb >= t.min_lsb) {
+                    // grid: the finest bit kept by the main accumulator. |x * 2^shift| < 2^kGridBits, and a chunk moves
+                    // at most 2^17 rows in and out of a cluster within 63 bits. Bits below the grid (wide columns) go to
+                    // the low accumulator, which keeps kLowBits more; anything finer cannot be summed exactly.
+                    int grid = t.max_msb - (kGridBits - 1);
+                    if (grid < t.min_lsb) grid = t.min_lsb;
+                    shift = -grid;
+                    if (t.min_lsb < grid) wide = 1;
+                    if (t.min_lsb < grid - kLowBits) atomicOr(&flags, RLS_STATUS_RANGE);
+                }
             }
         }
+        float *colmean = reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo);
+        int *colshift = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 128);
+        int *colwide = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 256);
+        // One power of two for all columns (distances keep their order): with |x - mean| < 2^(M+1) in every column the
+        // centred values obey |x - mean| * 2^(kScaledMsb - M - 2) < 2^(kScaledMsb - 1), one bit inside what fp16 holds for
+        // 2 c'.  The exponent is kept inside the fp32 range; data that small only makes every comparison a close call.
+        // (the 32 threads of the columns are the lower half of one wave: the exchange stays among them)
+        for (int off = 16; off >= 1; off >>= 1) msb = max(msb, __shfl_xor(msb, off, 64));
+        int e = kScaledMsb - 2 - (msb > -(1 << 20) ? msb : 0);
+        e = min(max(e, -100), 100);
+        const float scale = ldexpf(1.0f, e);
+        colmean[l] = -(mean * scale);      // what the kernels add after multiplying by the scale
+        colshift[l] = shift;
+        colwide[l] = wide;
+        if (l == 0) *reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo + kColScaleOff) = scale;
+        if (wide) atomicOr(&flags, 1 << 16);
     }
-    float *colmean = reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo);
-    int *colshift = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 128);
-    int *colwide = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 256);
-    // One power of two for all columns (distances keep their order): with |x - mean| < 2^(M+1) in every column the
-    // centred values obey |x - mean| * 2^(kScaledMsb - M - 2) < 2^(kScaledMsb - 1), one bit inside what fp16 holds for
-    // 2 c'.  The exponent is kept inside the fp32 range; data that small only makes every comparison a close call.
-    for (int off = 16; off >= 1; off >>= 1) msb = max(msb, __shfl_xor(msb, off, 64));
-    int e = kScaledMsb - 2 - (msb > -(1 << 20) ? msb : 0);
-    e = min(max(e, -100), 100);
-    const float scale = ldexpf(1.0f, e);
-    colmean[l] = -(mean * scale);      // what the kernels add after multiplying by the scale
-    colshift[l] = shift;
-    colwide[l] = wide;
-    if (l == 0) *reinterpret_cast<float *>(ws + (int64_t)b * ws_bs + off_colinfo + kColScaleOff) = scale;
-    if (wide) atomicOr(&flags, 1 << 16);
     __syncthreads();
-    if (l == 0) { colwide[32] = (flags >> 16) & 1; status[b] = flags & 0xffff; }
+    if (threadIdx.x == 0) {
+        int *colwide = reinterpret_cast<int *>(ws + (int64_t)b * ws_bs + off_colinfo + 256);
+        colwide[32] = (flags >> 16) & 1;
+        status[b] = flags & 0xffff;
+    }
 }
 
 // ---- the prepared copy of the points (see prep_block_u4_of): what the step kernel would derive from a row in every
@@ -1855,7 +1886,7 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     // column statistics
     hipLaunchKernelGGL(colstats_kernel, dim3(L.stat_blocks, batch), dim3(kThreads), 0, s, a.X, a.N, (int)a.d, DP, a.ldx,
                        a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
-    hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(32), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
+    hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(256), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
                        L.per_batch, L.colstat_part, L.colinfo, a.status);
     // Rounds after the first run on the prepared copy of the points - unless the loss of every round is wanted (that
     // pass needs every row), or the sweep is so light in distance work (a single k up to 32: one tile of centroids per
