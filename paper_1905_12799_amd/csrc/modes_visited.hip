@@ -82,17 +82,26 @@ __global__ void __launch_bounds__(kHistThreads) knob_hist_kernel(const float *__
         const int64_t i = r * stride + (int64_t)blockIdx.x * kHistThreads + tid;
         const bool valid = i < N;
         const float *row = X + (valid ? i : 0) * ldx;
-        for (int j = 0; j < dm.n_knobs; ++j) {
-            const int lo = offs[j], hi = offs[j + 1];
-            const int arg = valid ? nearest_entry(vals, lo, hi, row[j], unsorted[j] == 0) : -1;
-            if (hi - lo <= 8) {
-                // few entries: most lanes would hit the same counters; count per entry with a ballot instead
-                for (int v = lo; v < hi; ++v) {
-                    const int c = __popcll(__ballot(arg == v));
-                    if (lane == 0 && c) atomicAdd(&cnt[v], c);
+        // the knob columns of the row eight at a time: all eight loads are out before the first search starts
+        for (int j0 = 0; j0 < dm.n_knobs; j0 += 8) {
+            float xv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) xv[u] = row[min(j0 + u, dm.n_knobs - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + u;
+                if (j >= dm.n_knobs) break;              // same for every lane
+                const int lo = offs[j], hi = offs[j + 1];
+                const int arg = valid ? nearest_entry(vals, lo, hi, xv[u], unsorted[j] == 0) : -1;
+                if (hi - lo <= 8) {
+                    // few entries: most lanes would hit the same counters; count per entry with a ballot instead
+                    for (int v = lo; v < hi; ++v) {
+                        const int c = __popcll(__ballot(arg == v));
+                        if (lane == 0 && c) atomicAdd(&cnt[v], c);
+                    }
+                } else if (valid) {
+                    atomicAdd(&cnt[arg], 1);
                 }
-            } else if (valid) {
-                atomicAdd(&cnt[arg], 1);
             }
         }
     }
