@@ -586,10 +586,13 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
     // ---- the log of moved pairs (PRE): records [log_head, log_tail) of the ring are waiting
     int log_head = 0, log_tail = 0;                  // wave-uniform
     auto log_flush = [&](int nrec) {
-        // Works off `nrec` <= 64 records: DP lanes per record, one feature each - the row is read (a coalesced read of
-        // one row per record), put on the fixed-point grid and moved from the old cluster's accumulators to the new
-        // one's.  Integer adds: the order in which records are worked off does not matter.
-        constexpr int LPR = DP, RPS = 64 / LPR, STEPS = 64 / RPS, BATCH = STEPS < 8 ? STEPS : 8;   // rows in flight (16 costs more registers than it saves in waiting)
+        // Works off `nrec` <= 64 records: a few lanes per record, eight features each (four at d_pad = 8) - the row is
+        // read (16 bytes per load where rows can be read that way), put on the fixed-point grid and moved from the old
+        // cluster's accumulators to the new one's.  Integer adds: the order in which records are worked off does not
+        // matter.  What is the same for all lanes of a record (its fields, the row address, the accumulator rows) is
+        // worked out by 4 (2, 2) lanes instead of one per feature, and a flush is 4 (2, 2) steps of 16 (32, 32) records.
+        constexpr int FPL = DP >= 16 ? 8 : 4;   // features per lane
+        constexpr int LPR = DP / FPL, RPS = 64 / LPR, STEPS = 64 / RPS, BATCH = STEPS < 4 ? STEPS : 4;   // steps whose rows are in flight together
         // The records were written by other lanes of this wave: their stores must have been issued to the memory
         // system before the reads.  Both go through this compute unit's own first-level cache, so workgroup scope is
         // enough (a wider scope would write back the second-level cache, which costs more than the whole flush).
@@ -597,42 +600,64 @@ __device__ inline void wave_loop(const WaveCtx &c, double (&jloc)[8])
         unsigned long long rec = 0ull;
         if (lane < nrec) rec = __hip_atomic_load(&c.log[(unsigned)(log_head + lane) & (kLogCap - 1)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        const int l = lane % LPR, g = lane / LPR;
-        // this lane's feature column in its copy of the accumulators (the lane group picks the copy)
+        const int fq = FPL * (lane % LPR), g = lane / LPR;     // this lane's first feature, its record within a step
+        // this lane's feature columns in its copy of the accumulators (the lane group picks the copy)
         const int cp = g & (c.copies - 1);
-        unsigned long long *const scol = c.sums + (int64_t)cp * c.real_rows * (DP + 1) + l;
-        int *const ccol = c.cnts + cp * c.real_rows;
-        const float *const xcol = c.X + c.chunk_begin * c.ldx + l;
+        unsigned long long *const scol = c.sums + (int64_t)cp * c.real_rows * (DP + 1) + fq;
+        const float *const xcol = c.X + c.chunk_begin * c.ldx + fq;
+        // member counts: the lane that holds a record moves its one member, once per flush
+        if (lane < nrec) {
+            int *const ccol = c.cnts + (lane & (c.copies - 1)) * c.real_rows;
+            const int nrow = (int)(((unsigned)rec >> 17) & 0xfffu), orow = (int)((unsigned)(rec >> 32) & 0xffffu);
+            atomicAdd(ccol + nrow, 1);
+            if (orow != 0xffff) atomicAdd(ccol + orow, -1);
+        }
+        int pow2hi[FPL];
+#pragma unroll
+        for (int j = 0; j < FPL; ++j) pow2hi[j] = c.pow2hi_s[fq + j];
         for (int s0 = 0; s0 < STEPS && s0 * RPS < nrec; s0 += BATCH) {
             unsigned lo[BATCH], hi[BATCH];
-            float xv[BATCH];
+            float xv[BATCH][FPL];
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
                 const int src = (s0 + u) * RPS + g;
                 lo[u] = (unsigned)__shfl((int)(unsigned)rec, src, 64);
                 hi[u] = (unsigned)__shfl((int)(unsigned)(rec >> 32), src, 64);
-                const bool ok = src < nrec && l < d;
-                xv[u] = ok ? xcol[(int64_t)(lo[u] & 0x1ffffu) * c.ldx] : 0.0f;
+                const bool ok = src < nrec;
+                const float *const row = xcol + (int64_t)(lo[u] & 0x1ffffu) * c.ldx;
+                if (VEC) {
+#pragma unroll
+                    for (int h = 0; h < FPL / 4; ++h) {
+                        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                        if (ok && fq + 4 * h < d) v = *reinterpret_cast<const float4 *>(row + 4 * h);     // d is a multiple of four here
+                        xv[u][4 * h + 0] = v.x; xv[u][4 * h + 1] = v.y; xv[u][4 * h + 2] = v.z; xv[u][4 * h + 3] = v.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < FPL; ++j) xv[u][j] = (ok && fq + j < d) ? row[j] : 0.0f;
+                }
             }
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
                 const int src = (s0 + u) * RPS + g;
-                if (src < nrec && l < d) {
+                if (src < nrec) {
                     const int nrow = (int)((lo[u] >> 17) & 0xfffu), orow = (int)(hi[u] & 0xffffu);
-                    const unsigned long long v = any_wide ? (unsigned long long)to_fixed(xv[u], c.shift_s[l]) + kFixBias
-                                                          : fixed_biased(xv[u], c.pow2hi_s[l]);
-                    atomicAdd(scol + nrow * (DP + 1), v);
-                    if (l == 0) atomicAdd(ccol + nrow, 1);
-                    if (orow != 0xffff) {
-                        __hip_atomic_fetch_sub(scol + orow * (DP + 1), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                        if (l == 0) atomicAdd(ccol + orow, -1);
-                    }
-                    if (any_wide && c.wide_s[l] != 0) {
-                        // bits below the grid of a wide column go to a global integer accumulator (rare)
-                        const long long low = fixed_low(xv[u], c.shift_s[l]);
-                        if (low != 0) {
-                            if (orow != 0xffff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + orow) * d + l]), (unsigned long long)(-low));
-                            atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + nrow) * d + l]), (unsigned long long)low);
+                    unsigned long long *const srow_n = scol + nrow * (DP + 1);
+                    unsigned long long *const srow_o = scol + orow * (DP + 1);
+#pragma unroll
+                    for (int j = 0; j < FPL; ++j) {
+                        if (fq + j >= d) continue;
+                        const unsigned long long v = any_wide ? (unsigned long long)to_fixed(xv[u][j], c.shift_s[fq + j]) + kFixBias
+                                                              : fixed_biased(xv[u][j], pow2hi[j]);
+                        atomicAdd(srow_n + j, v);
+                        if (orow != 0xffff) __hip_atomic_fetch_sub(srow_o + j, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        if (any_wide && c.wide_s[fq + j] != 0) {
+                            // bits below the grid of a wide column go to a global integer accumulator (rare)
+                            const long long low = fixed_low(xv[u][j], c.shift_s[fq + j]);
+                            if (low != 0) {
+                                if (orow != 0xffff) atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + orow) * d + fq + j]), (unsigned long long)(-low));
+                                atomicAdd(reinterpret_cast<unsigned long long *>(&c.losum[(int64_t)(c.grow0 + nrow) * d + fq + j]), (unsigned long long)low);
+                            }
                         }
                     }
                 }
