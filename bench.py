@@ -20,7 +20,8 @@ spaces of 262,144 x 16 as well, with their own step counts stated inside).  Each
                 serves up to eight k), the matrix work actually issued, and - from rocprofv3 counters of this
                 library version, else null - the HBM bytes really moved and the vector-issue utilisation
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload, with the scaling to the sweep's mix of k
-  lloyd_step_per_k / early_exit   extra timings outside the timed steps
+  lloyd_step_per_k / early_exit / graph_replay   extra timings outside the timed steps (graph_replay: a short sweep
+                recorded into a HIP graph once and replayed, against the same sweep launched kernel by kernel)
 and the line ends with `hbm_copy_measured`: what a plain 1 GiB device-to-device copy moves per second on the same chip
 (bytes read + written), the attainable figure next to the 8 TB/s that the HBM fractions are quoted against.
 """
@@ -247,6 +248,39 @@ def run_workload(name, steps, warmup, args):
         torch.cuda.synchronize()
         out["early_exit"] = {"ms": (time.perf_counter() - t2) * 1e3 / 3, "chosen_k": k_e, "k_computed": n_done, "k_wave": 8}
 
+    if not batched and not args.no_graph and not (args.no_per_k and args.no_early_exit) and sweep_ms < 25.0:
+        # A sweep enqueues kernels only, so a caller can record it into a HIP graph once and replay it on new rows of the
+        # same shape.  Outside the timed steps: the recorded sweep replayed, against the same sweep launched kernel by
+        # kernel (short sweeps are bound by their launches: about 2 (k_max - 1) + 2 rounds + 8 of them).
+        side = torch.cuda.Stream()
+        side.wait_stream(main_stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            rls.kmeans_sweep(X, w.k_min, w.k_max, w.iters, seed=seeds[0], want_labels=want_labels, workspace=ws, check_status=False)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                g_res = rls.kmeans_sweep(X, w.k_min, w.k_max, w.iters, seed=seeds[0], want_labels=want_labels, workspace=ws,
+                                         check_status=False)
+        main_stream.wait_stream(side)
+        eager = rls.kmeans_sweep(X, w.k_min, w.k_max, w.iters, seed=seeds[0], want_labels=want_labels, workspace=ws, check_status=False)
+        torch.cuda.synchronize()
+        want_inertia = eager.inertia.clone()
+        reps = 20
+        graph.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(reps):
+            rls.kmeans_sweep(X, w.k_min, w.k_max, w.iters, seed=seeds[0], want_labels=want_labels, workspace=ws, check_status=False)
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        out["graph_replay"] = {"sweep_ms_replayed": (t3 - t2) * 1e3 / reps, "sweep_ms_launched": (t4 - t3) * 1e3 / reps,
+                               "same_result": bool(torch.equal(g_res.inertia, want_inertia))}
+        del graph, g_res, eager
+
     if not batched and not args.no_per_k:
         # The Lloyd step for one k at a time (outside the timed steps): where the launch time leaves the floor set by
         # reading the trajectory and starts to follow the distance work.  Same kernel, a plan with a single run; here
@@ -337,6 +371,7 @@ def main() -> int:
                     help="comma-separated further workloads for the `workloads` block (default: whole_layer and batched "
                          "next to large, large next to whole_layer; 'none' for the headline alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="leave out the graph-replay timing of short sweeps")
     ap.add_argument("--no-labels", action="store_true", help="do not write the per-k label arrays")
     ap.add_argument("--serial-score", action="store_true",
                     help="score on the main stream before the sweep instead of beside it on a second stream")
@@ -382,7 +417,7 @@ def main() -> int:
     }
     if "cpu_baseline" in h:
         out["cpu_baseline"] = h["cpu_baseline"]
-    for key in ("configs_scored_per_s", "sweep_config_iter_per_s", "stage_ms", "gbt_score", "early_exit", "lloyd_step_per_k"):
+    for key in ("configs_scored_per_s", "sweep_config_iter_per_s", "stage_ms", "gbt_score", "early_exit", "graph_replay", "lloyd_step_per_k"):
         if key in h:
             out[key] = h[key]
     out["library_version"] = rls.version()
