@@ -51,6 +51,7 @@ struct SweepPlan {
     int32_t total_rows;  // sum of k over the runs
     int32_t n_chunks;    // point chunks per group
     int32_t chunk_len;   // points per chunk (multiple of the tile size)
+    int32_t chunk_block; // chunks per block of the step kernel's workgroup order (all groups of a block of chunks, then the next block)
     int32_t dp;          // padded feature count: 8, 16 or 32
     GroupDesc g[kMaxGroups];
     uint8_t sched[kMaxGroups];   // launch order: group indices by falling cost
