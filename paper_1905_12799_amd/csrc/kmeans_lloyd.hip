@@ -114,6 +114,7 @@ struct StepArgs {
     int64_t ws_bs;           // bytes per batch element
     int64_t off_colinfo, off_opA, off_cnmax, off_psum, off_pcnt, off_pj, off_losum, off_prev, off_xp, off_log;
     int32_t first_round;     // 1: no point has a label yet (every pair enters a cluster, nothing leaves one)
+    int32_t batch;           // spaces swept by the launch
 };
 
 // x * 2^shift truncated toward zero, |x * 2^shift| < 2^kGridBits; exact whenever x is a multiple of 2^-shift.
@@ -1258,22 +1259,25 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int TH = step_threads_of(DP), WV = TH / 64;
 
-    const int b = blockIdx.y;
-    if (a.status[b] != 0) return;
-    // Workgroup order: the chunks are taken in blocks of plan.chunk_block; within a block the groups go heaviest first
-    // (the dispatcher hands workgroups out in index order, light ones fill the end), and the workgroups of all groups
-    // for one chunk sit a multiple of eight apart - they run at about the same time on the same XCD, so that what one
-    // of them reads of the chunk (its rows or its part of the prepared copy) the others find in that XCD's L2.
-    int gi, chunk;
+    // Workgroup order: the chunks of all spaces of the batch, numbered space by space, are taken in blocks of
+    // plan.chunk_block; within a block the groups go heaviest first (the dispatcher hands workgroups out in index order,
+    // light ones fill the end), and the workgroups of all groups for one chunk sit a multiple of eight apart - they run
+    // at about the same time on the same XCD, so that what one of them reads of the chunk (its rows or its part of the
+    // prepared copy) the others find in that XCD's L2.
+    int gi, chunk, b;
     {
         const int B = plan.chunk_block;
+        const int n_all = plan.n_chunks * a.batch;          // chunks of the whole batch
         const int per_block = B * plan.n_groups;
         const int blk = blockIdx.x / per_block, rem = blockIdx.x % per_block;
         const int c0 = blk * B;
-        const int bw = min(B, plan.n_chunks - c0);          // chunks of this block (the last one may be short)
+        const int bw = min(B, n_all - c0);                  // chunks of this block (the last one may be short)
         gi = plan.sched[rem / bw];
-        chunk = c0 + rem % bw;
+        const int vc = c0 + rem % bw;
+        b = vc / plan.n_chunks;
+        chunk = vc - b * plan.n_chunks;
     }
+    if (a.status[b] != 0) return;
     const GroupDesc g = plan.g[gi];
     const int d = a.d;
     const int k0 = plan.k_min + g.run0;                                   // k of the group's first run
@@ -1344,7 +1348,7 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
     c.sums = sums; c.cnts = cnts; c.copies = copies; c.real_rows = real_rows; c.mu_s = mu_s; c.shift_s = shift_s; c.pow2hi_s = pow2hi_s; c.wide_s = wide_s; c.cnmax_s = cnmax_s;
     c.scale = *reinterpret_cast<const float *>(wsb + a.off_colinfo + kColScaleOff);
     c.xp = reinterpret_cast<const uint4 *>(wsb + a.off_xp);
-    c.log = reinterpret_cast<unsigned long long *>(wsb + a.off_log) + ((int64_t)blockIdx.x * WV + (tid >> 6)) * kLogCap;
+    c.log = reinterpret_cast<unsigned long long *>(wsb + a.off_log) + ((int64_t)(gi * plan.n_chunks + chunk) * WV + (tid >> 6)) * kLogCap;
     c.X = Xb; c.ldx = a.ldx; c.N = a.N; c.d = d; c.k0 = k0; c.n_runs = g.n_runs; c.n_tiles = g.n_tiles; c.grow0 = grow0;
     c.prev = reinterpret_cast<unsigned char *>(wsb + a.off_prev) + (int64_t)g.lab0 * ((a.N + 15) / 16 * 16);
     c.labels_out = (FINAL && a.labels) ? a.labels + (int64_t)b * a.lab_bs + (int64_t)g.run0 * a.N : nullptr;
@@ -1972,7 +1976,8 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
         const size_t need = (size_t)carve_lds(DP, a.d, g.n_tiles, rr, g.copies).total;
         if (need > lds) lds = need;
     }
-    const dim3 grid(plan.n_groups * plan.n_chunks, batch);
+    const dim3 grid((unsigned)((int64_t)plan.n_groups * plan.n_chunks * batch), 1);
+    sa.batch = batch;
     const bool prof = profile_enabled();
     for (int t = 0; t < a.iters; ++t) {
         sa.first_round = t == 0 ? 1 : 0;
@@ -2105,8 +2110,10 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
     // (workgroups go to the eight XCDs in turn, so the groups of one chunk meet on one XCD)
     int32_t cb = (kFillWorkgroups + plan->n_groups - 1) / plan->n_groups;
     cb = (cb + 7) / 8 * 8;
-    if (cb > plan->n_chunks) cb = plan->n_chunks;
+    const int64_t n_all = (int64_t)plan->n_chunks * (batch > 0 ? batch : 1);     // chunks of all spaces of the batch
+    if (cb > n_all) cb = (int32_t)n_all;
     plan->chunk_block = cb;
+    if ((int64_t)plan->n_groups * n_all > 0x7fffffffLL) return RLS_ERR_INVALID_ARG;
     return RLS_OK;
 }
 
