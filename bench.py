@@ -46,10 +46,10 @@ VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4.0   # wave64 vector instructions per secon
 # library version they were taken with; any other version reports null.
 COUNTERS = {
     # mean over the 30 rounds of a sweep (first round included, like the launches the events time)
-    "whole_layer": {"version": 130, "fetch_kib": 100691.1, "write_kib": 61162.5, "fetch_scale": 2.0, "write_scale": 1.0,
-                    "valu_insts": 1.528e8},
-    "large": {"version": 130, "fetch_kib": 7447363.6, "write_kib": 913985.5, "fetch_scale": 2.0, "write_scale": 1.0,
-              "valu_insts": 4.771e9},
+    "whole_layer": {"version": 132, "fetch_kib": 190711.0, "write_kib": 44483.0, "fetch_scale": 2.0, "write_scale": 1.0,
+                    "valu_insts": 1.482e8},
+    "large": {"version": 132, "fetch_kib": 7470533.0, "write_kib": 912697.0, "fetch_scale": 2.0, "write_scale": 1.0,
+              "valu_insts": 4.776e9},
 }
 DEFAULT_STEPS = {"tiny": (50, 5), "mid": (20, 5), "whole_layer": (10, 3), "large": (5, 2), "batched": (5, 2)}
 

@@ -1276,6 +1276,12 @@ __global__ void __launch_bounds__(step_threads_of(DP)) lloyd_step_kernel(SweepPl
         const int vc = c0 + rem % bw;
         b = vc / plan.n_chunks;
         chunk = vc - b * plan.n_chunks;
+        // The division leaves these in vector registers although they are the same in every lane.  At d_pad 32 the
+        // kernel sits at the limit of 256 vector registers and spilled 35 of them over it (3% longer launches); as
+        // scalars they cost none.
+        b = __builtin_amdgcn_readfirstlane(b);
+        chunk = __builtin_amdgcn_readfirstlane(chunk);
+        gi = __builtin_amdgcn_readfirstlane(gi);
     }
     if (a.status[b] != 0) return;
     const GroupDesc g = plan.g[gi];
@@ -2086,13 +2092,13 @@ int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int3
         plan->sched[j] = v;
     }
     plan->total_rows = rows_before(k_min, plan->n_runs);
-    // chunks: enough workgroups over the whole batch to fill the chip several times over (a workgroup stages its
+    // chunks: enough workgroups over the whole batch to fill the chip twice over (a workgroup stages its
     // group's rows once, so more and shorter chunks only add set-up); a chunk never exceeds 2^16 points (the accumulators
     // would allow 2^17; with the groups of a chunk running side by side the shorter chunk measured 2% shorter launches at 8M x 32)
     const int tp = geo.tile_points;
     const int64_t tiles_total = (N + tp - 1) / tp;
     const int64_t units = (int64_t)plan->n_groups * (batch > 0 ? batch : 1);
-    int64_t want = (1024 + units - 1) / units;
+    int64_t want = (512 + units - 1) / units;       // two workgroups per compute unit (1024 measured 4% longer launches at 1M x 16, 256 22% longer)
     // a workgroup should have several slabs per wave to spread its set-up over: at least 4096 points per chunk
     // but never fewer workgroups than fill the chip
     int64_t most = (N + 4095) / 4096;

@@ -66,7 +66,7 @@ using namespace rls;
 
 extern "C" {
 
-int32_t rls_version(void) { return 130; }
+int32_t rls_version(void) { return 132; }
 
 const char *rls_error_string(int32_t code)
 {

@@ -71,7 +71,7 @@ LloydGeometry lloyd_geometry(int dp);
 int padded_d(int d);
 // LDS bytes of a group: operand tiles + centroid copy + exact-sum accumulators + fixed part
 int64_t lloyd_group_lds_bytes(int dp, int d, int n_tiles, int real_rows, int copies);
-// `batch`: spaces swept by the same launches (sizes the chunks so that the whole batch gives ~1024 workgroups)
+// `batch`: spaces swept by the same launches (sizes the chunks so that the whole batch gives ~512 workgroups)
 int32_t make_sweep_plan(int64_t N, int32_t d, int32_t k_min, int32_t k_max, int32_t batch, SweepPlan *plan);
 
 // Workspace carving for one sweep (all offsets in bytes from the workspace base, per batch element
