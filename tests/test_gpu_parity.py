@@ -480,6 +480,24 @@ def test_sweep_many_spaces(rls, orc, batch, N, d, k_max, iters):
         compare_sweep(orc, X[b], one, ref, 1, k_max)
 
 
+@pytest.mark.parametrize("batch,N,d,k_min,k_max,iters", [(3, 70000, 16, 1, 64, 2), (5, 33000, 32, 1, 40, 2), (17, 4100, 5, 3, 17, 2)])
+def test_sweep_batched_block_order(rls, orc, batch, N, d, k_min, k_max, iters):
+    """The workgroups of a launch take the chunks of all spaces in blocks (all groups of a block of chunks, then the
+    next block).  Shapes where the chunks of the batch do not fill a whole number of blocks, where a block spans
+    several spaces, and where a space ends inside a block: every space against the oracle."""
+    rng = np.random.default_rng(batch * 1000 + d)
+    c = rng.uniform(-20, 20, size=(batch, 11, d))
+    X = np.stack([c[b][rng.integers(0, 11, N)] + rng.standard_normal((N, d)) * 1.5 for b in range(batch)]).astype(np.float32)
+    seeds = [77 + 13 * b for b in range(batch)]
+    res = rls.kmeans_sweep_batched(dev(X), k_min, k_max, iters, seeds=seeds)
+    torch.cuda.synchronize()
+    lab, cen, J, st = res.labels.cpu(), res.centroids.cpu(), res.inertia.cpu(), res.status.cpu()
+    for b in range(batch):
+        ref = orc.kmeans_sweep(X[b], k_min, k_max, iters, seed=seeds[b])
+        one = rls.SweepResult(k_min, k_max, d, lab[b], cen[b], J[b], None, st[b:b + 1])
+        compare_sweep(orc, X[b], one, ref, k_min, k_max)
+
+
 def test_sweep_strided_unaligned_rows_and_small_d(rls, orc):
     # rows 11 floats apart and starting 4 bytes off a 16-byte boundary: the scalar load paths
     rng = np.random.default_rng(21)
