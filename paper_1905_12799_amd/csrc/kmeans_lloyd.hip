@@ -1930,16 +1930,18 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
     if (attr_status != hipSuccess) return attr_status;
     const int batch = a.batch;
     // column statistics
-    hipLaunchKernelGGL(colstats_kernel, dim3(L.stat_blocks, batch), dim3(kThreads), 0, s, a.X, a.N, (int)a.d, DP, a.ldx,
-                       a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
-    hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(256), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
-                       L.per_batch, L.colstat_part, L.colinfo, a.status);
+    if (!a.reuse_colstats) {
+        hipLaunchKernelGGL(colstats_kernel, dim3(L.stat_blocks, batch), dim3(kThreads), 0, s, a.X, a.N, (int)a.d, DP, a.ldx,
+                           a.x_batch_stride, a.ws, L.per_batch, L.colstat_part);
+        hipLaunchKernelGGL(colstats_final_kernel, dim3(batch), dim3(256), 0, s, a.N, (int)a.d, (int)L.stat_blocks, a.ws,
+                           L.per_batch, L.colstat_part, L.colinfo, a.status);
+    }
     // Rounds after the first run on the prepared copy of the points - unless the loss of every round is wanted (that
     // pass needs every row), or the sweep is so light in distance work (a single k up to 32: one tile of centroids per
     // group) that reading the rows is what it costs: the prepared copy is 6 to 12% larger than the rows.
     const bool trace = a.trace != nullptr;
-    const bool use_pre = !trace && a.iters >= 2 && plan.total_tiles >= 2 * plan.n_groups;
-    if (use_pre) {
+    const bool use_pre = sweep_uses_prepared(plan, a.iters, trace);
+    if (use_pre && !a.reuse_prepared) {
         // the prepared copy: one wave per block of 32 points, a few blocks per wave
         const int64_t n_blocks = (a.N + 31) / 32;
         int64_t grid_x = (n_blocks + 4 * 8 - 1) / (4 * 8);      // 4 waves per workgroup, ~8 blocks per wave
@@ -2015,6 +2017,11 @@ hipError_t launch_sweep_dp(const SweepPlan &plan, const SweepLayout &L, const Sw
 }  // namespace
 
 int padded_d(int d) { return d <= 8 ? 8 : (d <= 16 ? 16 : 32); }
+
+bool sweep_uses_prepared(const SweepPlan &plan, int32_t iters, bool trace)
+{
+    return !trace && iters >= 2 && plan.total_tiles >= 2 * plan.n_groups;
+}
 
 LloydGeometry lloyd_geometry(int dp)
 {
@@ -2138,6 +2145,7 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->bsum = take((int64_t)L->seed_blocks * 8);
     L->near = take(N);
     L->seedthr = take((int64_t)k_max * 8);
+    L->xp = take((N + 31) / 32 * prep_block_u4_of(plan.dp) * 16);     // (with the blocks above: the same place whatever the range of k)
     L->opA = take((int64_t)plan.total_tiles * tile_bytes_of(plan.dp));
     L->cnmax = take((int64_t)plan.n_runs * kMaxParts * 4);
     L->psum = take((int64_t)plan.n_chunks * plan.total_rows * d * 8);
@@ -2147,7 +2155,6 @@ void sweep_layout(const SweepPlan &plan, int64_t N, int32_t d, int32_t k_max, in
     L->tot = take((int64_t)plan.total_rows * d * 16);
     L->totcnt = take((int64_t)plan.total_rows * d * 8);
     L->prev = take((int64_t)plan.lab_slots * align_up(N, 16));
-    L->xp = take((N + 31) / 32 * prep_block_u4_of(plan.dp) * 16);
     L->log = take((int64_t)plan.n_groups * plan.n_chunks * (step_threads_of(plan.dp) / 64) * kLogCap * 8);
     L->per_batch = off;
     L->total = off * batch;

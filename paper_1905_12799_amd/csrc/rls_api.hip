@@ -66,7 +66,7 @@ using namespace rls;
 
 extern "C" {
 
-int32_t rls_version(void) { return 132; }
+int32_t rls_version(void) { return 133; }
 
 const char *rls_error_string(int32_t code)
 {
@@ -201,6 +201,7 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
     a.init_idx = init; a.init_batch_stride = init_bs;
     a.labels = labels_dev; a.centroids = centroids_dev; a.inertia = inertia_dev; a.trace = inertia_trace_dev;
     a.status = status_dev; a.ws = ws;
+    a.reuse_colstats = 0; a.reuse_prepared = 0;
     RLS_HIP_TRY(launch_sweep(plan, L, a, s));
     return RLS_OK;
 }
@@ -263,7 +264,7 @@ int32_t rls_kmeans_sweep_until_knee(const float *X_dev, int64_t N, int32_t d, in
 
     double previous_loss = INFINITY;
     int32_t chosen = k_max, n_done = 0, chain_done = 0;
-    bool fired = false;
+    bool fired = false, have_colstats = false, have_prepared = false;
     for (int32_t k_lo = k_min; k_lo <= k_max && !fired; k_lo += k_wave) {
         const int32_t k_hi = k_lo + k_wave - 1 < k_max ? k_lo + k_wave - 1 : k_max;
         SweepPlan plan;
@@ -288,7 +289,12 @@ int32_t rls_kmeans_sweep_until_knee(const float *X_dev, int64_t N, int32_t d, in
         a.inertia = inertia_dev + (k_lo - k_min);
         a.trace = nullptr;
         a.status = status_dev; a.ws = ws;
+        // every wave sweeps the same rows with the same workspace: column information and prepared copy are made once
+        a.reuse_colstats = have_colstats ? 1 : 0;
+        a.reuse_prepared = have_prepared ? 1 : 0;
         RLS_HIP_TRY(launch_sweep(plan, L, a, s));
+        have_colstats = true;
+        if (sweep_uses_prepared(plan, iters, false)) have_prepared = true;
         int32_t status_host = 0;
         RLS_HIP_TRY(hipMemcpyAsync(inertia_host + (k_lo - k_min), inertia_dev + (k_lo - k_min),
                                    (size_t)(k_hi - k_lo + 1) * sizeof(double), hipMemcpyDeviceToHost, s));

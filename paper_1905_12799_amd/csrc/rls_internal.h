@@ -153,11 +153,17 @@ struct SweepArgs {
     double *trace;                // [batch][n_runs][iters+1] or null
     int32_t *status;              // [batch]
     char *ws;                     // workspace base
+    // A sweep over the same rows with the same workspace has run before (the waves of a sweep that stops at the knee):
+    // the column information, and the prepared copy of the points, are still in place and are not made again.
+    int32_t reuse_colstats;
+    int32_t reuse_prepared;
 };
 // benchmark timing of the Lloyd step kernel (see rls_bench.h)
 bool profile_enabled();
 hipError_t profile_mark(hipStream_t s, bool begin);
 
 hipError_t launch_sweep(const SweepPlan &plan, const SweepLayout &L, const SweepArgs &a, hipStream_t s);
+// whether the rounds after the first of such a sweep read the prepared copy of the points
+bool sweep_uses_prepared(const SweepPlan &plan, int32_t iters, bool trace);
 
 }  // namespace rls

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(library):
 
 def test_version_and_error_strings(library):
     from paper_1905_12799_amd import binding
-    assert binding.version() == 132
+    assert binding.version() == 133
     assert binding.error_string(0) == "ok"
     for code in range(-6, 0):
         assert binding.error_string(code) not in ("ok", "unknown error code")
