@@ -179,7 +179,9 @@ int32_t rls_kmeans_sweep_batched(int32_t batch, const float *X_dev, int64_t N, i
  * this call SYNCHRONISES `stream`, copies the wave's losses to inertia_host and applies the test of rls_pick_knee in
  * k order.  The outputs for the k that were computed equal those of rls_kmeans_sweep over the whole range, and
  * *k_out equals rls_pick_knee on the whole curve: runs for different k do not depend on each other.
- *   k_wave        >= 1; a multiple of 8 keeps the MFMA tiles full
+ *   k_wave        >= 1; a multiple of 8 keeps the MFMA tiles full.  The k of a wave share each read of the points, and
+ *                 the waves of a call share the column statistics and the prepared copy of the points: larger waves
+ *                 cost less per k, smaller ones stop closer behind the knee
  *   seed / init_idx_dev  as rls_kmeans_sweep (the chain is extended wave by wave)
  *   labels_dev    [k_max-k_min+1][N] or null; centroids_dev, inertia_dev as rls_kmeans_sweep; only the first
  *                 *n_done_out runs are written
